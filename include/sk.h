@@ -1,0 +1,206 @@
+/*
+ * sk.h - C ABI of the stateful-session attention library for MI355X (gfx950).
+ *
+ * One attention layer of the paper's stateful-session model: a short segment of
+ * new tokens attends against a long, persistent, per-session KV cache.
+ *
+ *   data plane  (Alg. 1, "K.append(Forward(tokens, K))"; Sec. 3.4 "only the delta
+ *                is processed and appended"): sk_session_append commits the chunk's
+ *                K/V into the session cache and the chunk attends causally over
+ *                cache + chunk;
+ *   query plane (Alg. 2, "Forward(tokens_q, K)"; Sec. 3.2 Eq. 2; Sec. 3.3 Region 2;
+ *                Sec. 3.9.3 Extend/Clear): sk_session_query attends over the cache
+ *                and commits nothing;
+ *   both planes for many sessions in one step (Sec. 3.7 heterogeneous
+ *                PREFILL+DECODE batches): sk_batch_step;
+ *   a batch of registered questions sharing a prefix, evaluated against one session
+ *                after a data update (Alg. 3; Sec. 3.7 grouped prefill):
+ *                sk_session_query_shared_prefix.
+ *
+ * The result of every attention call is softmax(Q K^T * scale) V (Sec. 3.2 Eq. 1)
+ * with grouped-query mapping "query head h reads KV head h / (Hq/Hkv)" and causal
+ * limit "the token at absolute position p sees positions 0..p inclusive".
+ *
+ * General rules
+ *   - Every function returns SK_OK (0) or a negative sk_status; nothing throws,
+ *     aborts or synchronises the device unless stated.
+ *   - The caller owns every device buffer (kv_mem, workspace, q/k/v/out/lse).  The
+ *     library owns host metadata and the layout inside kv_mem and workspace.  The
+ *     library calls hipHostMalloc once per pool (a small pinned staging ring) and
+ *     never hipMalloc.
+ *   - Kernels are enqueued on the stream passed in (a hipStream_t cast to void*);
+ *     host metadata (lengths, block tables, free list) advances at enqueue time;
+ *     device results are valid once the stream reaches that point.  All calls on a
+ *     pool must be issued from one thread at a time and on one stream (or be
+ *     ordered externally), mirroring the paper's single GPU worker (Sec. 3.6).
+ *   - Device pointers must be 16-byte aligned.
+ *   - Same inputs, same block tables, same n_splits => bit-identical outputs.
+ *   - Token-major layouts: q [T][Hq][d], k and v [T][Hkv][d], out [T][Hq][d],
+ *     lse [T][Hq] (natural-log log-sum-exp of the scaled scores, float).
+ */
+#ifndef SK_H
+#define SK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum sk_status {
+    SK_OK = 0,
+    SK_E_INVAL = -1,      /* null/misaligned pointer, negative size, bad enum, repeated session */
+    SK_E_SHAPE = -2,      /* head counts / head_dim / block_tokens not supported */
+    SK_E_DTYPE = -3,
+    SK_E_NOMEM = -4,      /* pool out of blocks, sessions, or table space; nothing changed */
+    SK_E_BADSESSION = -5,
+    SK_E_EMPTY = -6,      /* softmax over zero keys (cache-only query on an empty session) */
+    SK_E_WORKSPACE = -7,  /* kv_mem / workspace too small, or step exceeds max_batch_tokens */
+    SK_E_HIP = -8,        /* a HIP runtime call failed; see sk_last_hip_error() */
+    SK_E_NODEVICE = -9    /* compute call on a metadata-only pool */
+} sk_status;
+
+enum { SK_F32 = 0, SK_BF16 = 1 };                       /* element types */
+enum { SK_OP_APPEND = 0, SK_OP_QUERY_A = 1, SK_OP_QUERY_B = 2 };  /* sk_batch_step ops */
+enum { SK_POOL_METADATA_ONLY = 1 };                     /* sk_pool_desc.flags */
+
+typedef struct sk_pool sk_pool;
+
+/*
+ * Pool description, filled by the caller.  The pool is the paper's unified KV cache
+ * (Sec. 3.7 "cells", Sec. 3.10.1) for ONE layer, cut into blocks of block_tokens
+ * tokens; a session owns a list of blocks (its block table).  Per token the pool
+ * stores 2 * n_kv_heads * head_dim elements (Sec. 5.3 with d = n_kv_heads*head_dim).
+ */
+typedef struct sk_pool_desc {
+    int32_t dtype;            /* SK_F32 | SK_BF16: type of q,k,v and of the cache (the
+                                 commit is a bit copy) */
+    int32_t n_q_heads;        /* multiple of n_kv_heads */
+    int32_t n_kv_heads;
+    int32_t head_dim;         /* 64 or 128 */
+    int32_t block_tokens;     /* power of two, 16..1024 */
+    int32_t max_sessions;     /* >= 1 */
+    int64_t n_blocks;         /* blocks in the pool */
+    int64_t max_session_tokens; /* longest session; 0 => n_blocks * block_tokens */
+    int32_t max_batch_tokens; /* most new tokens (appends + queries) in one call; 0 => 4096 */
+    int32_t flags;            /* 0 or SK_POOL_METADATA_ONLY (host bookkeeping only: no device
+                                 memory, compute calls only do their allocation part; lets a
+                                 scheduler rehearse admission, Sec. 3.7) */
+    float   softmax_scale;    /* 0 => 1/sqrt(head_dim) (Sec. 3.2 Eq. 1) */
+    int32_t reserved;
+    void*   kv_mem;           /* DEVICE, >= sk_pool_kv_bytes(desc), 256-byte aligned */
+    size_t  kv_bytes;
+    void*   workspace;        /* DEVICE, >= sk_pool_workspace_bytes(desc), 256-byte aligned:
+                                 device block tables, work lists, split partials, staging
+                                 for uncommitted query K/V */
+    size_t  workspace_bytes;
+} sk_pool_desc;
+
+/* Sizes implied by a description (kv_mem/workspace fields ignored).  0 on a bad description. */
+size_t sk_pool_kv_bytes(const sk_pool_desc* desc);
+size_t sk_pool_workspace_bytes(const sk_pool_desc* desc);
+
+/* Creates host metadata (and, unless metadata-only, a pinned staging ring on the current
+ * device; zeroes nothing in kv_mem).  *out is NULL on error. */
+int sk_pool_create(const sk_pool_desc* desc, sk_pool** out);
+/* Frees host metadata and the staging ring; caller memory is untouched.  The caller must
+ * have synchronised the stream(s) the pool was used on. */
+int sk_pool_destroy(sk_pool* pool);
+int sk_pool_blocks_free(const sk_pool* pool, int64_t* out);
+/* Replaces the free list by perm[0..n-1] (a permutation of 0..n_blocks-1; blocks are handed
+ * out in that order).  Only legal while no session owns a block.  Lets a harness reproduce
+ * fragmented, randomly permuted block tables. */
+int sk_pool_set_alloc_order(sk_pool* pool, const int32_t* perm, int64_t n);
+
+/* Sessions (Sec. 3.4).  Ids are small non-negative integers, reused after destroy. */
+int sk_session_create(sk_pool* pool, int32_t* out_id);
+int sk_session_destroy(sk_pool* pool, int32_t id);          /* blocks go back to the free list */
+int sk_session_length(const sk_pool* pool, int32_t id, int64_t* out_tokens);
+/* Host view of the block table, valid until the next call that changes the session. */
+int sk_session_block_table(const sk_pool* pool, int32_t id, const int32_t** table, int64_t* n_blocks);
+
+/*
+ * DATA PLANE (Alg. 1).  q [L][Hq][d], k,v [L][Hkv][d] DEVICE, pool dtype.  Commits k,v bit for
+ * bit at positions n..n+L-1 of the session and writes, for chunk token i, attention over
+ * positions 0..n+i.  out [L][Hq][d] of out_dtype (SK_F32 or the pool dtype); lse [L][Hq]
+ * float or NULL.  q/out may be NULL together: commit only.  All or nothing: on error the
+ * session, tables and free list are unchanged.  L == 0 is a no-op.  L <= max_batch_tokens.
+ */
+int sk_session_append(sk_pool* pool, int32_t id, const void* q, const void* k, const void* v,
+                      int32_t L, void* out, int out_dtype, float* lse, void* hip_stream);
+
+/*
+ * QUERY PLANE (Alg. 2; Sec. 3.2 Eq. 2).  Never changes kv_mem, tables or lengths.
+ * k == v == NULL: keys are the cache only, no mask (the literal Eq. 2).  k,v given
+ * [nq][Hkv][d]: the query's own tokens follow the cache causally and are dropped afterwards
+ * (Region 2, Sec. 3.3; Extend then Clear, Sec. 3.9.3); the output equals what
+ * sk_session_append would have written.  n_splits: partitions of the cached tokens
+ * processed by separate workgroups and merged by log-sum-exp; 0 = chosen by the library.
+ * An empty cache with k == NULL gives SK_E_EMPTY.  nq == 0 is a no-op.
+ */
+int sk_session_query(sk_pool* pool, int32_t id, const void* q, const void* k, const void* v,
+                     int32_t nq, void* out, int out_dtype, float* lse, int32_t n_splits,
+                     void* hip_stream);
+
+/*
+ * RAGGED MULTI-SESSION STEP (Sec. 3.7).  Item i owns packed token rows
+ * cu_tokens[i]..cu_tokens[i+1]-1 of q/k/v/out/lse; op[i] is SK_OP_APPEND, SK_OP_QUERY_A
+ * (cache only) or SK_OP_QUERY_B (own K/V, causal).  session_id, op, cu_tokens are HOST
+ * arrays.  A session may appear once per step.  Equal to issuing the items one by one
+ * (outputs up to summation order, cache bits exactly).  Block allocation is all or nothing
+ * for the whole step.
+ */
+int sk_batch_step(sk_pool* pool, int32_t n_items, const int32_t* session_id, const int32_t* op,
+                  const int32_t* cu_tokens, const void* q, const void* k, const void* v,
+                  void* out, int out_dtype, float* lse, void* hip_stream);
+
+/*
+ * REGISTERED-QUESTION BATCH (Alg. 3 loop body for all f_i at once; Sec. 3.7 grouped prefill).
+ * Question j = prefix (P tokens, shared) ++ suffix_j (Sfx tokens); each is evaluated like a
+ * query with own K/V; the prefix rows are computed once.  qp [P][Hq][d], kp,vp [P][Hkv][d],
+ * qs [NQ][Sfx][Hq][d], ks,vs [NQ][Sfx][Hkv][d]; out_prefix [P][Hq][d], out_suffix
+ * [NQ][Sfx][Hq][d]; lse_* float or NULL.  P may be 0.  Commits nothing.
+ */
+int sk_session_query_shared_prefix(sk_pool* pool, int32_t id,
+                                   const void* qp, const void* kp, const void* vp, int32_t P,
+                                   const void* qs, const void* ks, const void* vs,
+                                   int32_t NQ, int32_t Sfx,
+                                   void* out_prefix, void* out_suffix, int out_dtype,
+                                   float* lse_prefix, float* lse_suffix, void* hip_stream);
+
+/*
+ * Reads a session's committed K/V back in token order: k_out, v_out [count][Hkv][d] DEVICE,
+ * pool dtype, tokens first..first+count-1.  Bit copy through the block table (used to check
+ * the commit and to export a session).
+ */
+int sk_session_gather(const sk_pool* pool, int32_t id, int64_t first, int64_t count,
+                      void* k_out, void* v_out, void* hip_stream);
+
+/* Byte offset inside kv_mem of element (block, kv_head, is_v, slot, dim), so a harness can
+ * address the pool without knowing the layout.  Negative on bad arguments. */
+int64_t sk_pool_element_offset(const sk_pool* pool, int64_t block, int32_t kv_head, int32_t is_v,
+                               int32_t slot, int32_t dim);
+
+/* Counters since creation: tokens appended, query tokens, kernel launches, cached-token
+ * bytes the attention kernels were asked to stream. */
+typedef struct sk_pool_stats {
+    int64_t tokens_appended, tokens_queried, launches, kv_bytes_streamed;
+} sk_pool_stats;
+int sk_pool_get_stats(const sk_pool* pool, sk_pool_stats* out);
+
+/* Launch geometry of the most recent attention call (for checking that it depends on the
+ * shapes only, not on how the cache was built): workgroups, splits per row tile, row tiles. */
+typedef struct sk_launch_info {
+    int32_t workgroups, n_splits, row_tiles, kernel_variant;
+} sk_launch_info;
+int sk_pool_last_launch(const sk_pool* pool, sk_launch_info* out);
+
+const char* sk_strerror(int status);     /* static storage */
+int sk_last_hip_error(void);             /* hipError_t of the last failing HIP call in this thread */
+int sk_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SK_H */

@@ -1,0 +1,570 @@
+// Host side of the library: pool bookkeeping (free list, sessions, block tables), argument
+// checks, the planner that cuts a call into workgroups, and the C ABI of include/sk.h.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <deque>
+#include <new>
+#include <vector>
+
+#include "../../include/sk.h"
+#include "sk_internal.h"
+
+namespace {
+
+thread_local int g_last_hip = 0;
+
+constexpr int kRingSlots = 4;
+constexpr size_t kMetaBytes = 4u << 20;          // device region for uploaded lists (and ring slot size)
+constexpr int kPartSlotRows = 128;               // rows reserved per partial slot
+constexpr int kDefaultTargetWgs = 512;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int ilog2_exact(int64_t x) { int l = 0; while ((int64_t(1) << l) < x) ++l; return ((int64_t(1) << l) == x) ? l : -1; }
+
+struct Session {
+    bool live = false;
+    int64_t len = 0;
+    std::vector<int32_t> blocks;
+};
+
+struct Layout {
+    int elem = 0, G = 0;
+    int64_t head_stride = 0, blk_stride = 0, v_off = 0;
+    int64_t eph_head_stride = 0, eph_blk_stride = 0, eph_v_off = 0;
+    int64_t max_blocks_per_session = 0, max_session_tokens = 0;
+    int32_t max_batch_tokens = 0;
+    int64_t eph_blocks = 0;
+    int64_t part_slots = 0;
+    size_t kv_bytes = 0;
+    // workspace offsets
+    size_t off_tables = 0, off_meta = 0, off_part_ml = 0, off_part_o = 0, off_eph = 0, ws_bytes = 0;
+};
+
+bool derive_layout(const sk_pool_desc& d, Layout& L)
+{
+    if (d.dtype != SK_F32 && d.dtype != SK_BF16) return false;
+    if (d.n_kv_heads <= 0 || d.n_q_heads <= 0 || d.n_q_heads % d.n_kv_heads) return false;
+    if (d.head_dim != 64 && d.head_dim != 128) return false;
+    if (d.block_tokens < 16 || d.block_tokens > 1024 || ilog2_exact(d.block_tokens) < 0) return false;
+    if (d.n_blocks <= 0 || d.n_blocks > (int64_t(1) << 30) || d.max_sessions <= 0 || d.max_sessions > (1 << 20)) return false;
+    if (d.max_session_tokens < 0 || d.max_batch_tokens < 0) return false;
+    L.elem = d.dtype == SK_F32 ? 4 : 2;
+    L.G = d.n_q_heads / d.n_kv_heads;
+    L.v_off = int64_t(d.block_tokens) * d.head_dim * L.elem;
+    L.head_stride = 2 * L.v_off;
+    L.blk_stride = L.head_stride * d.n_kv_heads;
+    L.eph_v_off = int64_t(16) * d.head_dim * L.elem;
+    L.eph_head_stride = 2 * L.eph_v_off;
+    L.eph_blk_stride = L.eph_head_stride * d.n_kv_heads;
+    int64_t mst = d.max_session_tokens ? d.max_session_tokens : d.n_blocks * d.block_tokens;
+    mst = std::min<int64_t>(mst, d.n_blocks * d.block_tokens);
+    if (mst > (int64_t(1) << 29)) return false;       // positions are int32 with head room
+    L.max_session_tokens = mst;
+    L.max_blocks_per_session = (mst + d.block_tokens - 1) / d.block_tokens;
+    L.max_batch_tokens = d.max_batch_tokens ? d.max_batch_tokens : 4096;
+    if (L.max_batch_tokens > (1 << 20)) return false;
+    L.eph_blocks = (L.max_batch_tokens + 15) / 16 + std::max(d.max_sessions, 1024) + 1;
+    int64_t rows = int64_t(L.max_batch_tokens) * d.n_q_heads;
+    L.part_slots = 2048 + 2 * ((rows + kPartSlotRows - 1) / kPartSlotRows);
+    L.kv_bytes = size_t(L.blk_stride) * size_t(d.n_blocks);
+    size_t off = 0;
+    L.off_tables = off; off = align_up(off + size_t(d.max_sessions) * L.max_blocks_per_session * 4, 256);
+    L.off_meta = off;   off = align_up(off + kMetaBytes, 256);
+    L.off_part_ml = off; off = align_up(off + size_t(L.part_slots) * kPartSlotRows * 2 * 4, 256);
+    L.off_part_o = off; off = align_up(off + size_t(L.part_slots) * kPartSlotRows * d.head_dim * 4, 256);
+    L.off_eph = off;    off = align_up(off + size_t(L.eph_blocks) * L.eph_blk_stride, 256);
+    L.ws_bytes = off;
+    return true;
+}
+
+}  // namespace
+
+struct sk_pool {
+    sk_pool_desc d;
+    Layout L;
+    bool device = false;
+    std::deque<int32_t> free_blocks;
+    std::vector<Session> sessions;
+    std::vector<int32_t> free_ids;
+    int64_t blocks_in_use = 0;
+    // pinned staging ring for uploaded lists
+    unsigned char* ring = nullptr;
+    hipEvent_t ring_ev[kRingSlots] = {};
+    bool ring_used[kRingSlots] = {};
+    int ring_next = 0;
+    sk_geom geom;
+    sk_pool_stats stats = {};
+    sk_launch_info last = {};
+    int target_wgs = kDefaultTargetWgs;
+};
+
+namespace {
+
+#define SK_HIP(expr)                                        \
+    do {                                                    \
+        hipError_t e_ = (expr);                             \
+        if (e_ != hipSuccess) { g_last_hip = (int)e_; return SK_E_HIP; } \
+    } while (0)
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+Session* get_session(sk_pool* p, int32_t id)
+{
+    if (!p || id < 0 || id >= (int32_t)p->sessions.size() || !p->sessions[id].live) return nullptr;
+    return &p->sessions[id];
+}
+const Session* get_session(const sk_pool* p, int32_t id) { return get_session(const_cast<sk_pool*>(p), id); }
+
+int64_t blocks_needed(const sk_pool* p, int64_t len, int64_t add)
+{
+    const int64_t B = p->d.block_tokens;
+    return (len + add + B - 1) / B - (len + B - 1) / B;
+}
+
+// Takes a ring slot (waiting for the copy that last used it), returns its host pointer.
+int ring_acquire(sk_pool* p, int* slot, unsigned char** host)
+{
+    int s = p->ring_next;
+    p->ring_next = (s + 1) % kRingSlots;
+    if (p->ring_used[s]) SK_HIP(hipEventSynchronize(p->ring_ev[s]));
+    *slot = s;
+    *host = p->ring + size_t(s) * kMetaBytes;
+    return SK_OK;
+}
+
+int ring_upload(sk_pool* p, int slot, size_t bytes, hipStream_t st)
+{
+    unsigned char* dev = (unsigned char*)p->d.workspace + p->L.off_meta;
+    SK_HIP(hipMemcpyAsync(dev, p->ring + size_t(slot) * kMetaBytes, bytes, hipMemcpyHostToDevice, st));
+    SK_HIP(hipEventRecord(p->ring_ev[slot], st));
+    p->ring_used[slot] = true;
+    return SK_OK;
+}
+
+// Which attention kernel takes a tile of `max_rows` query rows per KV head.
+struct Variant { int id; int rows_per_slot; int tok_per_tile; };
+
+bool pick_variant(const sk_pool* p, int64_t n_tok, Variant& v)
+{
+    const int G = p->L.G;
+    const bool mfma_ok = p->d.dtype == SK_BF16 && p->d.head_dim == 128 && ilog2_exact(G) >= 0 && G <= 32;
+    const char* force_simple = getenv("SK_FORCE_SIMPLE");
+    if (mfma_ok && !(force_simple && force_simple[0] == '1')) {
+        if (n_tok * G > 64) { v.id = SK_KV_MFMA128; v.rows_per_slot = 128; v.tok_per_tile = 128 / G; }
+        else { v.id = SK_KV_MFMA64; v.rows_per_slot = 64; v.tok_per_tile = 64 / G; }
+        return true;
+    }
+    if (G > 16) return false;
+    v.id = SK_KV_SIMPLE; v.rows_per_slot = 16; v.tok_per_tile = std::max(1, 16 / G);
+    return true;
+}
+
+void fill_launch_common(const sk_pool* p, sk_launch& L, const void* q, void* out, int out_dtype, float* lse, const Variant& v)
+{
+    memset(&L, 0, sizeof L);
+    L.g = p->geom;
+    L.q = q; L.out = out; L.lse = lse;
+    unsigned char* ws = (unsigned char*)p->d.workspace;
+    L.part_ml = (float*)(ws + p->L.off_part_ml);
+    L.part_o = (float*)(ws + p->L.off_part_o);
+    L.out_dtype = out_dtype == SK_F32 ? 0 : 1;
+    L.rows_per_slot = v.rows_per_slot;
+}
+
+// Regular-mode attention over one session: n_tok new tokens at positions pos0.. (or no causal
+// limit), kv_len cached tokens, optionally one uncommitted segment already in staging block 0.
+int run_regular(sk_pool* p, int32_t id, const void* q, int64_t n_tok, int32_t pos0, int64_t kv_len,
+                int32_t eph_cnt, int32_t eph_pos0, void* out, int out_dtype, float* lse,
+                int32_t n_splits_req, hipStream_t st)
+{
+    Variant v;
+    if (!pick_variant(p, n_tok, v)) return SK_E_SHAPE;
+    sk_launch L;
+    fill_launch_common(p, L, q, out, out_dtype, lse, v);
+    L.mode = SK_MODE_REGULAR;
+    L.tbl_off = int32_t(int64_t(id) * p->L.max_blocks_per_session);
+    L.n_tok = (int32_t)n_tok;
+    L.tok_per_tile = v.tok_per_tile;
+    L.n_tiles = int32_t((n_tok + v.tok_per_tile - 1) / v.tok_per_tile);
+    L.pos0 = pos0;
+    L.kv_len = (int32_t)kv_len;
+    const int64_t base_wgs = int64_t(L.n_tiles) * p->d.n_kv_heads;
+    const int64_t slots_rows = p->L.part_slots * kPartSlotRows;
+    const int has_eph = eph_cnt > 0 ? 1 : 0;
+    int64_t S;
+    if (n_splits_req > 0) S = n_splits_req;
+    else S = std::max<int64_t>(1, (p->target_wgs + base_wgs / 2) / base_wgs);
+    int64_t chunk = kv_len > 0 ? (kv_len + S - 1) / S : 64;
+    if (n_splits_req <= 0) chunk = std::max<int64_t>(chunk, 256);    // at least four key tiles per workgroup
+    chunk = (chunk + 63) / 64 * 64;
+    S = kv_len > 0 ? (kv_len + chunk - 1) / chunk : 0;
+    int64_t parts = std::max<int64_t>(1, S + has_eph);
+    // respect the partial-slot capacity
+    while (parts > 1 && base_wgs * parts * v.rows_per_slot > slots_rows) {
+        chunk *= 2;
+        S = kv_len > 0 ? (kv_len + chunk - 1) / chunk : 0;
+        parts = std::max<int64_t>(1, S + has_eph);
+        if (S <= 1) break;
+    }
+    if (parts > 1 && base_wgs * parts * v.rows_per_slot > slots_rows) return SK_E_WORKSPACE;
+    L.chunk = (int32_t)chunk;
+    L.n_splits = (int32_t)parts;
+    L.eph_blk[0] = 0; L.eph_cnt[0] = eph_cnt; L.eph_pos0[0] = eph_pos0;
+    const int32_t wgs = int32_t(base_wgs * parts);
+    int e = sk_launch_attention(L, v.id, wgs, st);
+    if (e) { g_last_hip = e; return SK_E_HIP; }
+    p->stats.launches++;
+    if (parts > 1) {
+        e = sk_launch_combine(L, (int32_t)base_wgs, st);
+        if (e) { g_last_hip = e; return SK_E_HIP; }
+        p->stats.launches++;
+    }
+    p->stats.kv_bytes_streamed += kv_len * 2 * p->d.n_kv_heads * p->d.head_dim * p->L.elem * L.n_tiles;
+    p->last.workgroups = wgs; p->last.n_splits = (int32_t)parts; p->last.row_tiles = L.n_tiles; p->last.kernel_variant = v.id;
+    return SK_OK;
+}
+
+// Builds the scatter list for `count` tokens (packed rows src0..) going either behind position
+// `dst_tok0` of session `s` (blocks already in s->blocks) or into staging blocks eph_blk0..
+int build_scatter(const sk_pool* p, const Session* s, int32_t id, int64_t dst_tok0, int32_t src0, int64_t count,
+                  int64_t first_new_block, bool to_eph, int64_t eph_blk0, std::vector<sk_scatter>& out)
+{
+    const int64_t B = to_eph ? 16 : p->d.block_tokens;
+    for (int64_t t = dst_tok0; t < dst_tok0 + count;) {
+        const int64_t gend = std::min<int64_t>((t / 16 + 1) * 16, dst_tok0 + count);
+        sk_scatter it;
+        const int64_t bi = t / B;
+        it.src_tok0 = src0 + int32_t(t - dst_tok0);
+        it.count = int32_t(gend - t);
+        it.dst_slot0 = int32_t(t % B);
+        it.to_eph = to_eph ? 1 : 0;
+        if (to_eph) {
+            it.dst_off = (eph_blk0 + bi) * p->L.eph_blk_stride;
+            it.tbl_index = -1; it.block_id = 0;
+        } else {
+            const int32_t blk = s->blocks[bi];
+            it.dst_off = int64_t(blk) * p->L.blk_stride;
+            it.block_id = blk;
+            it.tbl_index = (bi >= first_new_block) ? int32_t(int64_t(id) * p->L.max_blocks_per_session + bi) : -1;
+        }
+        out.push_back(it);
+        t = gend;
+    }
+    return SK_OK;
+}
+
+int upload_and_scatter(sk_pool* p, const std::vector<sk_scatter>& items, const void* k, const void* v, hipStream_t st)
+{
+    if (items.empty()) return SK_OK;
+    const size_t bytes = items.size() * sizeof(sk_scatter);
+    if (bytes > kMetaBytes) return SK_E_WORKSPACE;
+    int slot; unsigned char* host;
+    int rc = ring_acquire(p, &slot, &host);
+    if (rc) return rc;
+    memcpy(host, items.data(), bytes);
+    rc = ring_upload(p, slot, bytes, st);
+    if (rc) return rc;
+    unsigned char* ws = (unsigned char*)p->d.workspace;
+    int e = sk_launch_scatter(p->geom, k, v, (const sk_scatter*)(ws + p->L.off_meta), (int32_t)items.size(),
+                              (int32_t*)(ws + p->L.off_tables), (unsigned char*)p->d.kv_mem, ws + p->L.off_eph, st);
+    if (e) { g_last_hip = e; return SK_E_HIP; }
+    p->stats.launches++;
+    return SK_OK;
+}
+
+// Takes `need` blocks for the session (caller has checked availability).
+void take_blocks(sk_pool* p, Session* s, int64_t need)
+{
+    for (int64_t i = 0; i < need; ++i) {
+        s->blocks.push_back(p->free_blocks.front());
+        p->free_blocks.pop_front();
+    }
+    p->blocks_in_use += need;
+}
+
+int check_out_dtype(const sk_pool* p, int out_dtype)
+{
+    if (out_dtype != SK_F32 && out_dtype != p->d.dtype) return SK_E_DTYPE;
+    return SK_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t sk_pool_kv_bytes(const sk_pool_desc* desc)
+{
+    Layout L;
+    if (!desc || !derive_layout(*desc, L)) return 0;
+    return L.kv_bytes;
+}
+
+size_t sk_pool_workspace_bytes(const sk_pool_desc* desc)
+{
+    Layout L;
+    if (!desc || !derive_layout(*desc, L)) return 0;
+    return L.ws_bytes;
+}
+
+int sk_pool_create(const sk_pool_desc* desc, sk_pool** out)
+{
+    if (out) *out = nullptr;
+    if (!desc || !out) return SK_E_INVAL;
+    if (desc->dtype != SK_F32 && desc->dtype != SK_BF16) return SK_E_DTYPE;
+    Layout L;
+    if (!derive_layout(*desc, L)) return SK_E_SHAPE;
+    const bool meta_only = (desc->flags & SK_POOL_METADATA_ONLY) != 0;
+    if (!meta_only) {
+        if (!desc->kv_mem || !desc->workspace) return SK_E_INVAL;
+        if ((reinterpret_cast<uintptr_t>(desc->kv_mem) & 255) || (reinterpret_cast<uintptr_t>(desc->workspace) & 255)) return SK_E_INVAL;
+        if (desc->kv_bytes < L.kv_bytes || desc->workspace_bytes < L.ws_bytes) return SK_E_WORKSPACE;
+    }
+    sk_pool* p = new (std::nothrow) sk_pool();
+    if (!p) return SK_E_NOMEM;
+    p->d = *desc;
+    p->L = L;
+    p->device = !meta_only;
+    for (int64_t i = 0; i < desc->n_blocks; ++i) p->free_blocks.push_back((int32_t)i);
+    p->sessions.resize(desc->max_sessions);
+    for (int32_t i = desc->max_sessions - 1; i >= 0; --i) p->free_ids.push_back(i);
+    const float scale = desc->softmax_scale != 0.f ? desc->softmax_scale : 1.0f / std::sqrt((float)desc->head_dim);
+    sk_geom& g = p->geom;
+    memset(&g, 0, sizeof g);
+    g.kv = (const unsigned char*)desc->kv_mem;
+    g.eph = meta_only ? nullptr : (const unsigned char*)desc->workspace + L.off_eph;
+    g.tables = meta_only ? nullptr : (const int32_t*)((const unsigned char*)desc->workspace + L.off_tables);
+    g.blk_stride = L.blk_stride; g.eph_blk_stride = L.eph_blk_stride;
+    g.head_stride = (int32_t)L.head_stride; g.v_off = (int32_t)L.v_off;
+    g.eph_head_stride = (int32_t)L.eph_head_stride; g.eph_v_off = (int32_t)L.eph_v_off;
+    g.B = desc->block_tokens; g.log2B = ilog2_exact(desc->block_tokens);
+    g.Hq = desc->n_q_heads; g.Hkv = desc->n_kv_heads; g.G = L.G; g.log2G = ilog2_exact(L.G);
+    g.d = desc->head_dim; g.elem = L.elem;
+    g.scale_log2e = scale * 1.4426950408889634f;
+    if (const char* t = getenv("SK_TARGET_WGS")) { int x = atoi(t); if (x > 0) p->target_wgs = x; }
+    if (!meta_only) {
+        hipError_t e = hipHostMalloc((void**)&p->ring, kMetaBytes * kRingSlots, hipHostMallocDefault);
+        if (e != hipSuccess) { g_last_hip = (int)e; delete p; return SK_E_HIP; }
+        for (int i = 0; i < kRingSlots; ++i) {
+            e = hipEventCreateWithFlags(&p->ring_ev[i], hipEventDisableTiming);
+            if (e != hipSuccess) { g_last_hip = (int)e; sk_pool_destroy(p); return SK_E_HIP; }
+        }
+    }
+    *out = p;
+    return SK_OK;
+}
+
+int sk_pool_destroy(sk_pool* p)
+{
+    if (!p) return SK_E_INVAL;
+    if (p->device) {
+        for (int i = 0; i < kRingSlots; ++i)
+            if (p->ring_ev[i]) (void)hipEventDestroy(p->ring_ev[i]);
+        if (p->ring) (void)hipHostFree(p->ring);
+    }
+    delete p;
+    return SK_OK;
+}
+
+int sk_pool_blocks_free(const sk_pool* p, int64_t* out)
+{
+    if (!p || !out) return SK_E_INVAL;
+    *out = (int64_t)p->free_blocks.size();
+    return SK_OK;
+}
+
+int sk_pool_set_alloc_order(sk_pool* p, const int32_t* perm, int64_t n)
+{
+    if (!p || !perm || n != p->d.n_blocks) return SK_E_INVAL;
+    if (p->blocks_in_use != 0) return SK_E_INVAL;
+    std::vector<char> seen((size_t)n, 0);
+    for (int64_t i = 0; i < n; ++i) {
+        if (perm[i] < 0 || perm[i] >= n || seen[perm[i]]) return SK_E_INVAL;
+        seen[perm[i]] = 1;
+    }
+    p->free_blocks.assign(perm, perm + n);
+    return SK_OK;
+}
+
+int sk_session_create(sk_pool* p, int32_t* out_id)
+{
+    if (!p || !out_id) return SK_E_INVAL;
+    if (p->free_ids.empty()) return SK_E_NOMEM;
+    int32_t id = p->free_ids.back();
+    p->free_ids.pop_back();
+    Session& s = p->sessions[id];
+    s.live = true; s.len = 0; s.blocks.clear();
+    *out_id = id;
+    return SK_OK;
+}
+
+int sk_session_destroy(sk_pool* p, int32_t id)
+{
+    Session* s = get_session(p, id);
+    if (!s) return p ? SK_E_BADSESSION : SK_E_INVAL;
+    for (int32_t b : s->blocks) p->free_blocks.push_back(b);
+    p->blocks_in_use -= (int64_t)s->blocks.size();
+    s->blocks.clear(); s->len = 0; s->live = false;
+    p->free_ids.push_back(id);
+    return SK_OK;
+}
+
+int sk_session_length(const sk_pool* p, int32_t id, int64_t* out)
+{
+    const Session* s = get_session(p, id);
+    if (!p || !out) return SK_E_INVAL;
+    if (!s) return SK_E_BADSESSION;
+    *out = s->len;
+    return SK_OK;
+}
+
+int sk_session_block_table(const sk_pool* p, int32_t id, const int32_t** table, int64_t* n_blocks)
+{
+    const Session* s = get_session(p, id);
+    if (!p || !table || !n_blocks) return SK_E_INVAL;
+    if (!s) return SK_E_BADSESSION;
+    *table = s->blocks.data();
+    *n_blocks = (int64_t)s->blocks.size();
+    return SK_OK;
+}
+
+int sk_session_append(sk_pool* p, int32_t id, const void* q, const void* k, const void* v, int32_t L,
+                      void* out, int out_dtype, float* lse, void* hip_stream)
+{
+    if (!p) return SK_E_INVAL;
+    Session* s = get_session(p, id);
+    if (!s) return SK_E_BADSESSION;
+    if (L < 0) return SK_E_INVAL;
+    if (L == 0) return SK_OK;
+    if (L > p->L.max_batch_tokens) return SK_E_WORKSPACE;
+    if (p->device) {
+        if (!k || !v || (!q) != (!out)) return SK_E_INVAL;
+        if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse)) return SK_E_INVAL;
+        if (q) { int rc = check_out_dtype(p, out_dtype); if (rc) return rc; }
+        Variant vv;
+        if (q && !pick_variant(p, L, vv)) return SK_E_SHAPE;
+    }
+    if (s->len + L > p->L.max_session_tokens) return SK_E_NOMEM;
+    const int64_t need = blocks_needed(p, s->len, L);
+    if (need > (int64_t)p->free_blocks.size()) return SK_E_NOMEM;
+    // from here on nothing can fail for lack of resources
+    const int64_t first_new = (int64_t)s->blocks.size();
+    const int64_t n = s->len;
+    take_blocks(p, s, need);
+    s->len = n + L;
+    p->stats.tokens_appended += L;
+    if (!p->device) return SK_OK;
+    hipStream_t st = (hipStream_t)hip_stream;
+    std::vector<sk_scatter> items;
+    build_scatter(p, s, id, n, 0, L, first_new, false, 0, items);
+    int rc = upload_and_scatter(p, items, k, v, st);
+    if (rc) return rc;
+    if (!q) return SK_OK;
+    return run_regular(p, id, q, L, (int32_t)n, n + L, 0, 0, out, out_dtype, lse, 0, st);
+}
+
+int sk_session_query(sk_pool* p, int32_t id, const void* q, const void* k, const void* v, int32_t nq,
+                     void* out, int out_dtype, float* lse, int32_t n_splits, void* hip_stream)
+{
+    if (!p) return SK_E_INVAL;
+    Session* s = get_session(p, id);
+    if (!s) return SK_E_BADSESSION;
+    if (nq < 0 || n_splits < 0) return SK_E_INVAL;
+    if (nq == 0) return SK_OK;
+    if (!p->device) return SK_E_NODEVICE;
+    if (!q || !out || (!k) != (!v)) return SK_E_INVAL;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse)) return SK_E_INVAL;
+    int rc = check_out_dtype(p, out_dtype);
+    if (rc) return rc;
+    if (nq > p->L.max_batch_tokens) return SK_E_WORKSPACE;
+    if (!k && s->len == 0) return SK_E_EMPTY;
+    Variant vv;
+    if (!pick_variant(p, nq, vv)) return SK_E_SHAPE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    p->stats.tokens_queried += nq;
+    if (k) {
+        std::vector<sk_scatter> items;
+        build_scatter(p, nullptr, id, 0, 0, nq, 0, true, 0, items);
+        rc = upload_and_scatter(p, items, k, v, st);
+        if (rc) return rc;
+        return run_regular(p, id, q, nq, (int32_t)s->len, s->len, nq, (int32_t)s->len, out, out_dtype, lse, n_splits, st);
+    }
+    return run_regular(p, id, q, nq, SK_NO_CAUSAL, s->len, 0, 0, out, out_dtype, lse, n_splits, st);
+}
+
+int sk_batch_step(sk_pool*, int32_t, const int32_t*, const int32_t*, const int32_t*, const void*, const void*,
+                  const void*, void*, int, float*, void*)
+{
+    return SK_E_INVAL;   // implemented in a later change
+}
+
+int sk_session_query_shared_prefix(sk_pool*, int32_t, const void*, const void*, const void*, int32_t,
+                                   const void*, const void*, const void*, int32_t, int32_t,
+                                   void*, void*, int, float*, float*, void*)
+{
+    return SK_E_INVAL;   // implemented in a later change
+}
+
+int sk_session_gather(const sk_pool* p, int32_t id, int64_t first, int64_t count, void* k_out, void* v_out, void* hip_stream)
+{
+    if (!p) return SK_E_INVAL;
+    const Session* s = get_session(p, id);
+    if (!s) return SK_E_BADSESSION;
+    if (!p->device) return SK_E_NODEVICE;
+    if (first < 0 || count < 0 || first + count > s->len) return SK_E_INVAL;
+    if (count == 0) return SK_OK;
+    if (!k_out || !v_out || !aligned16(k_out) || !aligned16(v_out)) return SK_E_INVAL;
+    int e = sk_launch_gather(p->geom, int32_t(int64_t(id) * p->L.max_blocks_per_session), first, count, k_out, v_out, hip_stream);
+    if (e) { g_last_hip = e; return SK_E_HIP; }
+    return SK_OK;
+}
+
+int64_t sk_pool_element_offset(const sk_pool* p, int64_t block, int32_t kv_head, int32_t is_v, int32_t slot, int32_t dim)
+{
+    if (!p || block < 0 || block >= p->d.n_blocks || kv_head < 0 || kv_head >= p->d.n_kv_heads ||
+        slot < 0 || slot >= p->d.block_tokens || dim < 0 || dim >= p->d.head_dim) return -1;
+    int64_t off = block * p->L.blk_stride + int64_t(kv_head) * p->L.head_stride;
+    if (!is_v) return off + (int64_t(slot) * p->d.head_dim + dim) * p->L.elem;
+    off += p->L.v_off;
+    if (p->d.dtype == SK_BF16) return off + (int64_t(dim) * p->d.block_tokens + slot) * p->L.elem;
+    return off + (int64_t(slot) * p->d.head_dim + dim) * p->L.elem;
+}
+
+int sk_pool_get_stats(const sk_pool* p, sk_pool_stats* out)
+{
+    if (!p || !out) return SK_E_INVAL;
+    *out = p->stats;
+    return SK_OK;
+}
+
+int sk_pool_last_launch(const sk_pool* p, sk_launch_info* out)
+{
+    if (!p || !out) return SK_E_INVAL;
+    *out = p->last;
+    return SK_OK;
+}
+
+const char* sk_strerror(int status)
+{
+    switch (status) {
+    case SK_OK: return "ok";
+    case SK_E_INVAL: return "invalid argument";
+    case SK_E_SHAPE: return "unsupported shape";
+    case SK_E_DTYPE: return "unsupported element type";
+    case SK_E_NOMEM: return "pool exhausted";
+    case SK_E_BADSESSION: return "no such session";
+    case SK_E_EMPTY: return "softmax over zero keys";
+    case SK_E_WORKSPACE: return "buffer too small for this call";
+    case SK_E_HIP: return "HIP runtime error";
+    case SK_E_NODEVICE: return "metadata-only pool";
+    default: return "unknown status";
+    }
+}
+
+int sk_last_hip_error(void) { return g_last_hip; }
+int sk_version(void) { return 1; }
+
+}  // extern "C"

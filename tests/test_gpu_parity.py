@@ -1,0 +1,134 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle, element by element, on
+the same seeded inputs.  Sizes span several key tiles, several row tiles and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+from workloads import synth
+from gpu_common import Pair, compare, dev
+
+pytestmark = pytest.mark.gpu
+
+
+def test_cfg1_fp32_single_session_every_step():
+    """Workload 1: fp32, 4/4 heads, d=64; 16 appends of 64 tokens to 1,024 cached tokens, then 4
+    non-committing queries of 16 tokens (cache-only and with own K/V); parity on every step."""
+    shape = synth.CFG1
+    gen = synth.generator(1)
+    pr = Pair(shape, block_tokens=16, n_blocks=80, kv_fill=0xFF)       # 0xFF bytes = NaN canaries
+    sid = pr.create()
+    for step in range(16):
+        q, k, v = synth.draw_qkv(gen, 64, shape)
+        pr.append(sid, q, k, v, name="cfg1 append %d" % step)
+    pr.check_cache(sid)
+    before = pr.pool.kv_mem.clone()
+    for i in range(4):
+        q, k, v = synth.draw_qkv(gen, 16, shape)
+        pr.query(sid, q, name="cfg1 query A %d" % i)
+        pr.query(sid, q, k, v, name="cfg1 query B %d" % i)
+        pr.query(sid, q, n_splits=3, name="cfg1 query A splits=3 %d" % i)
+    torch.cuda.synchronize()
+    assert torch.equal(before, pr.pool.kv_mem)
+    assert pr.pool.sk_session_length(sid) == 1024
+
+
+@pytest.mark.parametrize("block_tokens", [16, 64])
+def test_bf16_gqa_ragged_appends_and_queries(block_tokens):
+    """Llama-3-8B-shaped layer (32/8 heads, d=128, bf16) at a size the oracle finishes in seconds:
+    appends of ragged lengths (several row tiles, partial tiles, single tokens, block-straddling),
+    then queries of several lengths in both modes with several split counts."""
+    shape = synth.CFG2
+    gen = synth.generator(2, stream=1)
+    pr = Pair(shape, block_tokens=block_tokens, n_blocks=4096 // block_tokens + 8, kv_fill=0xFF, max_batch_tokens=1024)
+    sid = pr.create()
+    for i, L in enumerate([256, 100, 7, 1, 333, 64, 15, 1000]):
+        q, k, v = synth.draw_qkv(gen, L, shape)
+        pr.append(sid, q, k, v, name="append %d (L=%d)" % (i, L))
+    pr.check_cache(sid)
+    n = pr.pool.sk_session_length(sid)
+    assert n == 1776
+    before = pr.pool.kv_mem.clone()
+    for nq in [32, 16, 1, 5, 64, 100]:
+        q, k, v = synth.draw_qkv(gen, nq, shape)
+        pr.query(sid, q, name="query A nq=%d" % nq)
+        pr.query(sid, q, k, v, name="query B nq=%d" % nq)
+        for S in (1, 2, 7):
+            pr.query(sid, q, n_splits=S, name="query A nq=%d S=%d" % (nq, S))
+            pr.query(sid, q, k, v, n_splits=S, name="query B nq=%d S=%d" % (nq, S))
+    torch.cuda.synchronize()
+    assert torch.equal(before, pr.pool.kv_mem)
+
+
+def test_bf16_first_tokens_short_context():
+    """Short contexts (n < 16), where the bf16 rounding of the softmax weights weighs most, and
+    the very first token of an empty session (output = its own value)."""
+    shape = synth.CFG2
+    gen = synth.generator(2, stream=2)
+    pr = Pair(shape, n_blocks=16, kv_fill=0xFF)
+    sid = pr.create()
+    q, k, v = synth.draw_qkv(gen, 1, shape)
+    out, lse = pr.append(sid, q, k, v, name="first token")
+    G = shape.group
+    torch.cuda.synchronize()
+    expect = v.float().repeat_interleave(G, dim=1)
+    assert torch.equal(out.cpu(), expect)
+    for L in [1, 2, 3, 5]:
+        q, k, v = synth.draw_qkv(gen, L, shape)
+        pr.append(sid, q, k, v, name="short append L=%d" % L)
+    q, k, v = synth.draw_qkv(gen, 3, shape)
+    pr.query(sid, q, name="short query A")
+    pr.query(sid, q, k, v, name="short query B")
+    pr.check_cache(sid)
+
+
+def test_bf16_output_dtype_bf16_and_no_lse():
+    shape = synth.CFG2
+    gen = synth.generator(2, stream=3)
+    pr = Pair(shape, n_blocks=64)
+    sid = pr.create()
+    q, k, v = synth.draw_qkv(gen, 300, shape)
+    out, lse = pr.append(sid, q, k, v, out_dtype="bf16", want_lse=False)
+    assert out.dtype == torch.bfloat16 and lse is None
+    q, k, v = synth.draw_qkv(gen, 32, shape)
+    pr.query(sid, q, out_dtype="bf16", n_splits=4, name="bf16 out, split")
+    pr.query(sid, q, out_dtype="bf16", n_splits=1, name="bf16 out, direct")
+
+
+@pytest.mark.parametrize("shape", [synth.Shape("bf16", 8, 8, 64), synth.Shape("bf16", 12, 4, 128),
+                                   synth.Shape("f32", 8, 2, 128), synth.Shape("bf16", 64, 8, 128),
+                                   synth.Shape("bf16", 8, 8, 128)])
+def test_other_shapes(shape):
+    """head_dim 64 and a group size that is not a power of two go through the fp32-FMA kernel;
+    G = 8 and G = 1 go through the MFMA kernel."""
+    gen = synth.generator(9, stream=shape.n_q_heads)
+    pr = Pair(shape, n_blocks=64)
+    sid = pr.create()
+    for L in [70, 3, 130]:
+        q, k, v = synth.draw_qkv(gen, L, shape)
+        pr.append(sid, q, k, v, name="append L=%d" % L)
+    pr.check_cache(sid)
+    q, k, v = synth.draw_qkv(gen, 9, shape)
+    pr.query(sid, q, name="query A")
+    pr.query(sid, q, k, v, n_splits=2, name="query B")
+
+
+def test_large_logits_and_needle():
+    """Queries scaled by 8 (scores of magnitude ~8 sigma) prove the max subtraction; a planted key
+    aligned with the query at several positions (first, last, block and split boundaries) must
+    return that key's value: exact retrieval from mid-context (the paper's Q6 idea, Sec. 4.3)."""
+    shape = synth.CFG2
+    gen = synth.generator(2, stream=4)
+    n = 2048
+    for pos in [0, 15, 16, 511, 512, 1023, 1024, n - 1]:
+        pr = Pair(shape, n_blocks=n // 16 + 4)
+        sid = pr.create()
+        q, k, v = synth.draw_qkv(gen, n, shape)
+        qq, _, _ = synth.draw_qkv(gen, 4, shape, scale=8.0)
+        # plant: key at `pos` of KV head 2 is 4x query row (token 1, head 9); head 9 reads KV head 2
+        k[pos, 2] = (4.0 * qq[1, 9].float()).to(torch.bfloat16)
+        pr.append(sid, q[:1024], k[:1024], v[:1024], check=False)
+        pr.append(sid, q[1024:], k[1024:], v[1024:], check=False)
+        out, _ = pr.query(sid, qq, n_splits=4, name="needle pos=%d" % pos)
+        torch.cuda.synchronize()
+        got = out[1, 9].cpu()
+        assert torch.allclose(got, v[pos, 2].float(), atol=1e-2), "needle at %d not retrieved" % pos

@@ -1,0 +1,149 @@
+"""Host-side logic of the library, exercised without a GPU through a metadata-only pool:
+C-ABI exports, sizes, the block allocator (all-or-nothing, reuse, permuted order), session
+life cycle, argument checks."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2605_13784_amd as sk
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def meta_pool(**kw):
+    args = dict(dtype="bf16", n_q_heads=32, n_kv_heads=8, head_dim=128, block_tokens=16, n_blocks=64,
+                max_sessions=4, metadata_only=True)
+    args.update(kw)
+    return sk.Pool(**args)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "sk.h")).read()
+    declared = set(re.findall(r"\b(sk_[a-z_]+)\s*\(", header))
+    declared -= {"sk_pool_desc", "sk_pool_stats", "sk_launch_info", "sk_status", "sk_pool"}
+    assert declared == set(sk.EXPORTS)
+    L = sk.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert L.sk_version() >= 1
+
+
+def test_memory_model_matches_paper_formula():
+    """Sec. 5.3: M_KV = 2 * L * d * n_ctx * sizeof.  Per layer, with d = n_kv_heads*head_dim = 4096,
+    32K tokens, 2-byte elements: 2*4096*32768*2 bytes; times L = 32 layers is the printed ~17 GB."""
+    golden = open(os.path.join(ROOT, "tests", "golden", "memory_model.txt")).read()
+    per_session = int(re.search(r"M_KV_bytes\s*=\s*(\d+)", golden).group(1))
+    assert per_session == 2 * 32 * 4096 * 32768 * 2
+    desc = sk.make_desc("bf16", 32, 32, 128, 16, 32768 // 16)
+    assert sk.sk_pool_kv_bytes(desc) * 32 == per_session
+    assert round(per_session / 1e9) == 17
+    # grouped-query shape of the workloads: 8 KV heads -> a quarter of that, 4096 bytes per token
+    desc = sk.make_desc("bf16", 32, 8, 128, 16, 32768 // 16)
+    assert sk.sk_pool_kv_bytes(desc) == 32768 * 4096
+
+
+def test_bad_descriptions_are_rejected():
+    assert sk.sk_pool_kv_bytes(sk.make_desc("bf16", 32, 5, 128, 16, 8)) == 0      # heads not divisible
+    assert sk.sk_pool_kv_bytes(sk.make_desc("bf16", 32, 8, 96, 16, 8)) == 0       # head_dim
+    assert sk.sk_pool_kv_bytes(sk.make_desc("bf16", 32, 8, 128, 24, 8)) == 0      # block not power of two
+    assert sk.sk_pool_kv_bytes(sk.make_desc("bf16", 32, 8, 128, 8, 8)) == 0       # block too small
+    assert sk.sk_pool_kv_bytes(sk.make_desc("bf16", 32, 8, 128, 16, 0)) == 0
+    with pytest.raises(sk.SkError):
+        meta_pool(head_dim=100)
+    # a device pool needs memory
+    d = sk.make_desc("f32", 4, 4, 64, 16, 8)
+    h = ctypes.c_void_p()
+    assert sk.lib().sk_pool_create(ctypes.byref(d), ctypes.byref(h)) == sk.SK_E_INVAL
+    assert not h.value
+
+
+def test_allocator_all_or_nothing_and_reuse():
+    p = meta_pool(n_blocks=10, block_tokens=16)
+    a, b = p.sk_session_create(), p.sk_session_create()
+    assert p.sk_pool_blocks_free() == 10
+    p.reserve(a, 17)                       # 2 blocks
+    assert p.sk_session_length(a) == 17 and p.sk_session_block_table(a) == [0, 1]
+    p.reserve(a, 15)                       # fills block 1 exactly
+    assert p.sk_session_length(a) == 32 and len(p.sk_session_block_table(a)) == 2
+    p.reserve(b, 1)
+    assert p.sk_session_block_table(b) == [2]
+    p.reserve(a, 1)
+    assert p.sk_session_block_table(a) == [0, 1, 3]
+    assert p.sk_pool_blocks_free() == 6
+    # needs 7 blocks, 6 free: refused, nothing changes
+    before = (p.sk_session_length(a), p.sk_session_block_table(a), p.sk_pool_blocks_free())
+    with pytest.raises(sk.SkError) as e:
+        p.reserve(a, 15 + 16 * 6 + 1)
+    assert e.value.status == sk.SK_E_NOMEM
+    assert before == (p.sk_session_length(a), p.sk_session_block_table(a), p.sk_pool_blocks_free())
+    p.reserve(a, 15 + 16 * 6)              # exactly fits
+    assert p.sk_pool_blocks_free() == 0
+    with pytest.raises(sk.SkError):
+        p.reserve(b, 16)                   # b has 15 slots left in its block, 16 needs one more
+    p.reserve(b, 15)
+    # destroy returns blocks; they are reused in return order
+    p.sk_session_destroy(a)
+    assert p.sk_pool_blocks_free() == 9
+    c = p.sk_session_create()
+    assert c == a                          # ids are reused
+    assert p.sk_session_length(c) == 0
+    p.reserve(c, 16)
+    assert p.sk_session_block_table(c) == [0]
+    with pytest.raises(sk.SkError) as e:
+        p.sk_session_length(3)
+    assert e.value.status == sk.SK_E_BADSESSION
+
+
+def test_permuted_alloc_order_and_its_checks():
+    p = meta_pool(n_blocks=8)
+    p.sk_pool_set_alloc_order([7, 3, 5, 1, 0, 2, 4, 6])
+    a, b = p.sk_session_create(), p.sk_session_create()
+    p.reserve(a, 16); p.reserve(b, 16); p.reserve(a, 16); p.reserve(b, 32)
+    assert p.sk_session_block_table(a) == [7, 5]
+    assert p.sk_session_block_table(b) == [3, 1, 0]
+    with pytest.raises(sk.SkError):
+        p.sk_pool_set_alloc_order(list(range(8)))          # blocks in use
+    q = meta_pool(n_blocks=4)
+    with pytest.raises(sk.SkError):
+        q.sk_pool_set_alloc_order([0, 1, 2])                # wrong length
+    with pytest.raises(sk.SkError):
+        q.sk_pool_set_alloc_order([0, 1, 1, 2])             # not a permutation
+
+
+def test_session_limits():
+    p = meta_pool(max_sessions=2, n_blocks=100, max_session_tokens=40, max_batch_tokens=64)
+    a, b = p.sk_session_create(), p.sk_session_create()
+    with pytest.raises(sk.SkError) as e:
+        p.sk_session_create()
+    assert e.value.status == sk.SK_E_NOMEM
+    p.reserve(a, 40)
+    with pytest.raises(sk.SkError) as e:
+        p.reserve(a, 1)                                      # longest session reached
+    assert e.value.status == sk.SK_E_NOMEM
+    with pytest.raises(sk.SkError) as e:
+        p.reserve(b, 65)                                     # more than max_batch_tokens in one call
+    assert e.value.status == sk.SK_E_WORKSPACE
+    p.reserve(b, 0)                                          # no-op
+    assert p.sk_session_length(b) == 0
+    # compute calls on a metadata-only pool say so
+    h = p.h
+    rc = sk.lib().sk_session_query(h, a, None, None, None, 4, None, 0, None, 0, None)
+    assert rc == sk.SK_E_NODEVICE
+    assert sk.lib().sk_session_query(h, a, None, None, None, -1, None, 0, None, 0, None) == sk.SK_E_INVAL
+    assert sk.lib().sk_strerror(sk.SK_E_NOMEM).decode() == "pool exhausted"
+
+
+def test_element_offsets_describe_the_layout():
+    p = meta_pool(n_blocks=4, block_tokens=16)
+    e = 2
+    blk = 8 * 2 * 16 * 128 * e
+    assert p.sk_pool_element_offset(0, 0, False, 0, 0) == 0
+    assert p.sk_pool_element_offset(1, 0, False, 0, 0) == blk
+    assert p.sk_pool_element_offset(0, 1, False, 0, 0) == 2 * 16 * 128 * e
+    assert p.sk_pool_element_offset(0, 0, False, 3, 5) == (3 * 128 + 5) * e
+    assert p.sk_pool_element_offset(0, 0, True, 3, 5) == 16 * 128 * e + (5 * 16 + 3) * e    # V is [dim][token]
+    assert p.sk_pool_element_offset(4, 0, False, 0, 0) == -1
+    f = meta_pool(dtype="f32", n_q_heads=4, n_kv_heads=4, head_dim=64, n_blocks=4)
+    assert f.sk_pool_element_offset(0, 0, True, 3, 5) == 16 * 64 * 4 + (3 * 64 + 5) * 4       # V is [token][dim]
