@@ -177,6 +177,15 @@ int sk_session_query_shared_prefix(sk_pool* pool, int32_t id,
 int sk_session_gather(const sk_pool* pool, int32_t id, int64_t first, int64_t count,
                       void* k_out, void* v_out, void* hip_stream);
 
+/*
+ * Drops every cached token at position >= new_length: the SeqRemove(s, p, infinity) of
+ * Sec. 3.9.3 / Alg. 3, by which a caller can also reproduce the literal Strip / Extend / Clear
+ * cycle (append, read the output, truncate).  Host metadata only: whole blocks past the new
+ * end return to the free list, no device work, kv_mem bytes are not touched.
+ * new_length > current length gives SK_E_INVAL.
+ */
+int sk_session_truncate(sk_pool* pool, int32_t id, int64_t new_length);
+
 /* Byte offset inside kv_mem of element (block, kv_head, is_v, slot, dim), so a harness can
  * address the pool without knowing the layout.  Negative on bad arguments. */
 int64_t sk_pool_element_offset(const sk_pool* pool, int64_t block, int32_t kv_head, int32_t is_v,
@@ -195,6 +204,22 @@ typedef struct sk_launch_info {
     int32_t workgroups, n_splits, row_tiles, kernel_variant;
 } sk_launch_info;
 int sk_pool_last_launch(const sk_pool* pool, sk_launch_info* out);
+
+/*
+ * Optional timing of the kernels themselves, for benchmarks: while enabled, every attention
+ * call records HIP events on its stream before and after the attention kernel and after the
+ * combine kernel.  sk_pool_read_profile waits for the recorded events, returns the sums since
+ * the last read (and, if the arrays are given, the first `capacity` calls one by one, in call
+ * order, in milliseconds) and clears them.  At most 4096 calls are kept between reads.
+ */
+typedef struct sk_profile {
+    int64_t calls;
+    double attention_ms;   /* attention kernel(s) */
+    double combine_ms;     /* cross-split combine kernel(s) */
+} sk_profile;
+int sk_pool_set_profiling(sk_pool* pool, int enable);
+int sk_pool_read_profile(sk_pool* pool, sk_profile* out, float* attention_ms_per_call /*HOST or NULL*/,
+                         float* combine_ms_per_call /*HOST or NULL*/, int32_t capacity);
 
 const char* sk_strerror(int status);     /* static storage */
 int sk_last_hip_error(void);             /* hipError_t of the last failing HIP call in this thread */

@@ -156,6 +156,13 @@ class OracleSession:
             lse_s[j] = l[P:]
         return out_p, lse_p, out_s, lse_s
 
+    def truncate(self, new_length):
+        """SeqRemove(s, p, infinity) of Sec. 3.9.3: forget every token at position >= new_length."""
+        if new_length < 0 or new_length > self.length:
+            raise ValueError("new_length out of range")
+        self.K = self.K[:new_length].copy()
+        self.V = self.V[:new_length].copy()
+
     def cache(self):
         """Copies of the committed keys and values, [n,Hkv,d] raw bits."""
         return self.K.copy(), self.V.copy()

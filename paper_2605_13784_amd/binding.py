@@ -50,11 +50,16 @@ class sk_launch_info(ctypes.Structure):
                 ("row_tiles", ctypes.c_int32), ("kernel_variant", ctypes.c_int32)]
 
 
+class sk_profile(ctypes.Structure):
+    _fields_ = [("calls", ctypes.c_int64), ("attention_ms", ctypes.c_double), ("combine_ms", ctypes.c_double)]
+
+
 EXPORTS = [
     "sk_pool_kv_bytes", "sk_pool_workspace_bytes", "sk_pool_create", "sk_pool_destroy",
     "sk_pool_blocks_free", "sk_pool_set_alloc_order", "sk_session_create", "sk_session_destroy",
     "sk_session_length", "sk_session_block_table", "sk_session_append", "sk_session_query",
     "sk_batch_step", "sk_session_query_shared_prefix", "sk_session_gather",
+    "sk_session_truncate", "sk_pool_set_profiling", "sk_pool_read_profile",
     "sk_pool_element_offset", "sk_pool_get_stats", "sk_pool_last_launch", "sk_strerror",
     "sk_last_hip_error", "sk_version",
 ]
@@ -94,6 +99,9 @@ def lib():
     L.sk_session_query_shared_prefix.argtypes = [vp, i32, vp, vp, vp, i32, vp, vp, vp, i32, i32,
                                                  vp, vp, ctypes.c_int, vp, vp, vp]
     L.sk_session_gather.argtypes = [vp, i32, i64, i64, vp, vp, vp]
+    L.sk_session_truncate.argtypes = [vp, i32, i64]
+    L.sk_pool_set_profiling.argtypes = [vp, ctypes.c_int]
+    L.sk_pool_read_profile.argtypes = [vp, P(sk_profile), P(ctypes.c_float), P(ctypes.c_float), i32]
     L.sk_pool_element_offset.restype = i64
     L.sk_pool_element_offset.argtypes = [vp, i64, i32, i32, i32, i32]
     L.sk_pool_get_stats.argtypes = [vp, P(sk_pool_stats)]
@@ -226,6 +234,22 @@ class Pool:
         n = ctypes.c_int64()
         _ck(lib().sk_session_block_table(self.h, sid, ctypes.byref(tbl), ctypes.byref(n)), "sk_session_block_table")
         return [tbl[i] for i in range(n.value)]
+
+    def sk_session_truncate(self, sid, new_length):
+        _ck(lib().sk_session_truncate(self.h, sid, int(new_length)), "sk_session_truncate")
+
+    def sk_pool_set_profiling(self, enable):
+        _ck(lib().sk_pool_set_profiling(self.h, int(bool(enable))), "sk_pool_set_profiling")
+
+    def sk_pool_read_profile(self):
+        """-> (sums dict, per-call attention ms list, per-call combine ms list)"""
+        s = sk_profile()
+        cap = 4096
+        a = (ctypes.c_float * cap)()
+        c = (ctypes.c_float * cap)()
+        _ck(lib().sk_pool_read_profile(self.h, ctypes.byref(s), a, c, cap), "sk_pool_read_profile")
+        n = min(cap, s.calls)
+        return {k: getattr(s, k) for k, _ in s._fields_}, list(a[:n]), list(c[:n])
 
     def sk_pool_get_stats(self):
         s = sk_pool_stats()

@@ -100,6 +100,10 @@ struct sk_pool {
     sk_pool_stats stats = {};
     sk_launch_info last = {};
     int target_wgs = kDefaultTargetWgs;
+    // optional kernel timing
+    bool profiling = false;
+    std::vector<hipEvent_t> prof_ev;     // triples: before attention, after attention, after combine
+    size_t prof_used = 0;                // events in use
 };
 
 namespace {
@@ -143,6 +147,21 @@ int ring_upload(sk_pool* p, int slot, size_t bytes, hipStream_t st)
     SK_HIP(hipEventRecord(p->ring_ev[slot], st));
     p->ring_used[slot] = true;
     return SK_OK;
+}
+
+// With profiling on, reserves three events for this call and records the first.
+hipEvent_t* prof_begin(sk_pool* p, hipStream_t st)
+{
+    if (!p->profiling || p->prof_used + 3 > 3 * 4096) return nullptr;
+    while (p->prof_ev.size() < p->prof_used + 3) {
+        hipEvent_t ev;
+        if (hipEventCreate(&ev) != hipSuccess) return nullptr;
+        p->prof_ev.push_back(ev);
+    }
+    hipEvent_t* pe = &p->prof_ev[p->prof_used];
+    p->prof_used += 3;
+    (void)hipEventRecord(pe[0], st);
+    return pe;
 }
 
 // Which attention kernel takes a tile of `max_rows` query rows per KV head.
@@ -215,14 +234,17 @@ int run_regular(sk_pool* p, int32_t id, const void* q, int64_t n_tok, int32_t po
     L.n_splits = (int32_t)parts;
     L.eph_blk[0] = 0; L.eph_cnt[0] = eph_cnt; L.eph_pos0[0] = eph_pos0;
     const int32_t wgs = int32_t(base_wgs * parts);
+    hipEvent_t* pe = prof_begin(p, st);
     int e = sk_launch_attention(L, v.id, wgs, st);
     if (e) { g_last_hip = e; return SK_E_HIP; }
     p->stats.launches++;
+    if (pe) (void)hipEventRecord(pe[1], st);
     if (parts > 1) {
         e = sk_launch_combine(L, (int32_t)base_wgs, st);
         if (e) { g_last_hip = e; return SK_E_HIP; }
         p->stats.launches++;
     }
+    if (pe) (void)hipEventRecord(pe[2], st);
     p->stats.kv_bytes_streamed += kv_len * 2 * p->d.n_kv_heads * p->d.head_dim * p->L.elem * L.n_tiles;
     p->last.workgroups = wgs; p->last.n_splits = (int32_t)parts; p->last.row_tiles = L.n_tiles; p->last.kernel_variant = v.id;
     return SK_OK;
@@ -363,6 +385,7 @@ int sk_pool_destroy(sk_pool* p)
     if (p->device) {
         for (int i = 0; i < kRingSlots; ++i)
             if (p->ring_ev[i]) (void)hipEventDestroy(p->ring_ev[i]);
+        for (hipEvent_t ev : p->prof_ev) (void)hipEventDestroy(ev);
         if (p->ring) (void)hipHostFree(p->ring);
     }
     delete p;
@@ -519,6 +542,49 @@ int sk_session_gather(const sk_pool* p, int32_t id, int64_t first, int64_t count
     if (!k_out || !v_out || !aligned16(k_out) || !aligned16(v_out)) return SK_E_INVAL;
     int e = sk_launch_gather(p->geom, int32_t(int64_t(id) * p->L.max_blocks_per_session), first, count, k_out, v_out, hip_stream);
     if (e) { g_last_hip = e; return SK_E_HIP; }
+    return SK_OK;
+}
+
+int sk_session_truncate(sk_pool* p, int32_t id, int64_t new_length)
+{
+    if (!p) return SK_E_INVAL;
+    Session* s = get_session(p, id);
+    if (!s) return SK_E_BADSESSION;
+    if (new_length < 0 || new_length > s->len) return SK_E_INVAL;
+    const int64_t B = p->d.block_tokens;
+    const size_t keep = size_t((new_length + B - 1) / B);
+    while (s->blocks.size() > keep) {
+        p->free_blocks.push_back(s->blocks.back());
+        s->blocks.pop_back();
+        p->blocks_in_use--;
+    }
+    s->len = new_length;
+    return SK_OK;
+}
+
+int sk_pool_set_profiling(sk_pool* p, int enable)
+{
+    if (!p || !p->device) return p ? SK_E_NODEVICE : SK_E_INVAL;
+    p->profiling = enable != 0;
+    return SK_OK;
+}
+
+int sk_pool_read_profile(sk_pool* p, sk_profile* out, float* attn_pc, float* comb_pc, int32_t capacity)
+{
+    if (!p || !out) return SK_E_INVAL;
+    out->calls = 0; out->attention_ms = 0; out->combine_ms = 0;
+    for (size_t i = 0; i + 3 <= p->prof_used; i += 3) {
+        float a = 0.f, c = 0.f;
+        SK_HIP(hipEventSynchronize(p->prof_ev[i + 2]));
+        SK_HIP(hipEventElapsedTime(&a, p->prof_ev[i], p->prof_ev[i + 1]));
+        SK_HIP(hipEventElapsedTime(&c, p->prof_ev[i + 1], p->prof_ev[i + 2]));
+        if (out->calls < capacity) {
+            if (attn_pc) attn_pc[out->calls] = a;
+            if (comb_pc) comb_pc[out->calls] = c;
+        }
+        out->calls++; out->attention_ms += a; out->combine_ms += c;
+    }
+    p->prof_used = 0;
     return SK_OK;
 }
 

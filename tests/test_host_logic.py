@@ -22,7 +22,7 @@ def meta_pool(**kw):
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "sk.h")).read()
     declared = set(re.findall(r"\b(sk_[a-z_]+)\s*\(", header))
-    declared -= {"sk_pool_desc", "sk_pool_stats", "sk_launch_info", "sk_status", "sk_pool"}
+    declared -= {"sk_pool_desc", "sk_pool_stats", "sk_launch_info", "sk_status", "sk_pool", "sk_profile"}
     assert declared == set(sk.EXPORTS)
     L = sk.lib()
     for name in declared:
@@ -147,3 +147,19 @@ def test_element_offsets_describe_the_layout():
     assert p.sk_pool_element_offset(4, 0, False, 0, 0) == -1
     f = meta_pool(dtype="f32", n_q_heads=4, n_kv_heads=4, head_dim=64, n_blocks=4)
     assert f.sk_pool_element_offset(0, 0, True, 3, 5) == 16 * 64 * 4 + (3 * 64 + 5) * 4       # V is [token][dim]
+
+
+def test_truncate_returns_whole_blocks_only():
+    p = meta_pool(n_blocks=8)
+    a = p.sk_session_create()
+    p.reserve(a, 40)                        # blocks 0,1,2
+    p.sk_session_truncate(a, 33)
+    assert p.sk_session_length(a) == 33 and p.sk_session_block_table(a) == [0, 1, 2]
+    p.sk_session_truncate(a, 32)
+    assert p.sk_session_block_table(a) == [0, 1] and p.sk_pool_blocks_free() == 6
+    p.sk_session_truncate(a, 0)
+    assert p.sk_session_block_table(a) == [] and p.sk_pool_blocks_free() == 8
+    with pytest.raises(sk.SkError):
+        p.sk_session_truncate(a, 1)         # cannot grow
+    p.reserve(a, 16)
+    assert p.sk_session_block_table(a) == [3]          # freed blocks queue behind the untouched ones
