@@ -7,13 +7,14 @@
 // ---------------------------------------------------------------------------------------------
 // Pool geometry (constant for the life of a pool).
 //
-// kv_mem layout, chosen for gfx950: [block][kv_head][ K | V ] with, per (block, kv_head),
+// kv_mem layout, chosen for gfx950: [kv_head][block][ K | V ] with, per (head, block),
 //   K : [block_tokens][head_dim]            one 128/256-byte row per token
 //   V : bf16 pools  [head_dim][block_tokens]  (transposed: 8 consecutive tokens of one
 //                   dimension are one 16-byte MFMA operand for the P*V contraction)
 //       f32 pools   [block_tokens][head_dim]
-// so a 16-token group of one head is a contiguous 4 KiB (bf16, d=128, B=16) for K and for V
-// and every global load is a whole 128-byte line.
+// so a 16-token group of one head is a contiguous 4 KiB (bf16, d=128) for K and for V, every
+// global load is a whole 128-byte line, and the blocks of one head (what one workgroup
+// streams) are contiguous when a session's table is in order.
 // The staging area for uncommitted (query-plane) K/V in the workspace has the same layout
 // with 16-token blocks and an identity block table.
 // ---------------------------------------------------------------------------------------------
@@ -21,11 +22,12 @@ struct sk_geom {
     const unsigned char* kv;      // pool base
     const unsigned char* eph;     // staging base (workspace)
     const int32_t* tables;        // device block tables, [max_sessions][max_blocks_per_session]
-    int64_t blk_stride;           // bytes per pool block
-    int64_t eph_blk_stride;       // bytes per staging block (16 tokens)
-    int32_t head_stride;          // bytes per (block, head) in the pool
+    const int32_t* eph_ident;     // identity table 0,1,2,.. over the staging blocks
+    int64_t blk_stride;           // bytes from one block to the next (same head)
+    int64_t head_stride;          // bytes from one KV head to the next (same block)
+    int64_t eph_blk_stride;       // the same two for the staging area (16-token blocks)
+    int64_t eph_head_stride;
     int32_t v_off;                // byte offset of V inside (block, head)
-    int32_t eph_head_stride;
     int32_t eph_v_off;
     int32_t B, log2B;             // pool block_tokens
     int32_t Hq, Hkv, G, log2G;    // log2G = -1 when G is not a power of two

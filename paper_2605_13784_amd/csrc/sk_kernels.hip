@@ -70,12 +70,13 @@ __device__ __forceinline__ bool sk_decode_work(const sk_launch& P, int b, sk_wor
 }
 
 // A run of keys the kernel walks through in 16-token groups: either cached tokens of a session
-// (through its block table) or an uncommitted segment in the staging area (identity table).
+// (through its block table) or an uncommitted segment in the staging area (through a slice of
+// an identity table, so both kinds are addressed the same way).
 struct sk_seg {
     const unsigned char* base;   // + head offset already applied
-    const int32_t* table;        // nullptr: block = blk0 + (t >> log2B)
+    const int32_t* table;        // block of token t = table[t >> log2B]
     int64_t blk_stride;
-    int32_t blk0, v_off, B, log2B;
+    int32_t v_off, B, log2B;
     int32_t begin, end;          // token indices; begin is a multiple of 16
     int32_t pos_shift;           // absolute position = token index + pos_shift
 };
@@ -85,34 +86,54 @@ __device__ __forceinline__ sk_seg sk_make_seg(const sk_launch& P, const sk_work&
     sk_seg g;
     if (s == 0) {
         g.base = P.g.kv + (int64_t)w.kv_head * P.g.head_stride;
-        g.table = P.g.tables + w.tbl_off; g.blk_stride = P.g.blk_stride; g.blk0 = 0;
+        g.table = P.g.tables + w.tbl_off; g.blk_stride = P.g.blk_stride;
         g.v_off = P.g.v_off; g.B = P.g.B; g.log2B = P.g.log2B;
         g.begin = w.kv_begin; g.end = w.kv_end; g.pos_shift = 0;
     } else {
         g.base = P.g.eph + (int64_t)w.kv_head * P.g.eph_head_stride;
-        g.table = nullptr; g.blk_stride = P.g.eph_blk_stride; g.blk0 = w.eph_blk[s - 1];
+        g.table = P.g.eph_ident + (s == 1 ? w.eph_blk[0] : w.eph_blk[1]); g.blk_stride = P.g.eph_blk_stride;
         g.v_off = P.g.eph_v_off; g.B = 16; g.log2B = 4;
-        g.begin = 0; g.end = w.eph_cnt[s - 1]; g.pos_shift = w.eph_pos0[s - 1];
+        g.begin = 0; g.end = (s == 1 ? w.eph_cnt[0] : w.eph_cnt[1]); g.pos_shift = (s == 1 ? w.eph_pos0[0] : w.eph_pos0[1]);
     }
     return g;
 }
 
 __device__ __forceinline__ const unsigned char* sk_group_base(const sk_seg& g, int tg)
 {   // base of the block holding the 16-token group that starts at token tg (tg < g.end)
-    int blk = g.table ? g.table[tg >> g.log2B] : g.blk0 + (tg >> g.log2B);
+    // Block tables are only written by the commit kernel of an earlier launch, so inside an
+    // attention kernel they are constant: reading them through the constant address space makes
+    // the lookup a scalar load (it must not count as a vector memory operation, see below).
+    typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+    const int blk = ((const_i32_ptr)(uintptr_t)g.table)[tg >> g.log2B];
     return g.base + (int64_t)blk * g.blk_stride;
 }
 
 // ---------------------------------------------------------------------------------------------
 // bf16 MFMA attention kernel, head_dim 128.
 //
-// Workgroup = 4 waves.  A tile of 64 keys is staged in LDS (K rows swizzled by 16-byte chunk,
-// V^T rows swizzled by half) from registers that were loaded one tile ahead.  Waves are
-// arranged as NRG row groups x NPH key phases (NRG*NPH = 4): a row group owns 32 query rows,
-// a phase owns 64/NPH keys of every tile.  Per 32 keys a wave issues
-//   S^T[32 keys][32 rows]  = K[32][128] * Q^T[128][32]      8 x mfma_f32_32x32x16_bf16
+// Workgroup = 4 waves, arranged as NRG row groups x NPH key phases (NRG * NPH = 4): a row group
+// owns 32 query rows, a phase owns every NPH-th key tile.
+//
+// Keys move HBM -> LDS with direct-to-LDS loads (global_load_lds_dwordx4), never through
+// registers, into a ring of four 32-key tiles (K 8 KiB + V^T 8 KiB each).  One iteration
+// consumes two tiles (64 keys: both by every wave when NPH = 1, one per phase when NPH = 2)
+// while the other two are in flight, 32 KiB per workgroup and 64 KiB per CU, which is what
+// covers the HBM latency.  A direct-to-LDS load writes lane i's 16 bytes at
+// base + 16 i, so the bank swizzle is applied to the *source* address each lane picks:
+//   K   : LDS row rho holds global 16-byte chunk (c ^ (rho & 15)) at chunk position c,
+//   V^T : LDS row dd of a 16-key group holds the two 8-key halves swapped when bit 3 of dd is set.
+// The loads of one tile are issued by all four waves (4 instructions each); a wave waits on its
+// own vmcnt and a workgroup barrier publishes the tile.  Nothing else in the loop is a vector
+// memory instruction (block-table entries are scalar loads), so the outstanding-load count a
+// wave waits for is exact.
+// Tiles past the end of a segment re-read its last 16-key group (always valid memory); their
+// keys are masked by position.  The commit kernel zero-fills V behind the last committed key of
+// a 16-key group, so a masked key never contributes 0 * garbage.
+//
+// Per 32 keys a wave issues
+//   S^T[32 keys][32 rows]  = K[32][128] * Q^T[128][32]        8 x mfma_f32_32x32x16_bf16
 //   O^T[128][32 rows]     += V^T[128][32 keys] * P^T[32][32]  8 x mfma_f32_32x32x16_bf16
-// With S transposed a lane owns one query row (lane%32) and 16 keys of it, so the row maximum
+// With S transposed a lane owns one query row (lane % 32) and 16 keys of it, so the row maximum
 // and sum need one cross-lane exchange (lane ^ 32) and P feeds the second contraction straight
 // from registers.  Key row rho of the first product is loaded from key tau(rho) (bits 2 and 3
 // swapped) so that the 8 P values a lane hands to one PV instruction belong to 8 consecutive
@@ -121,61 +142,105 @@ __device__ __forceinline__ const unsigned char* sk_group_base(const sk_seg& g, i
 // exceeds it by more than SK_RESCALE_SLACK, which keeps exp2 arguments <= the slack and makes
 // accumulator rescaling rare; the result is the same up to rounding.
 // ---------------------------------------------------------------------------------------------
-#define SK_TK 64
+#define SK_TILE 32                 // keys per tile
+#define SK_TILE_BYTES 16384        // K 8 KiB | V^T 8 KiB
+#ifndef SK_NST
+#define SK_NST 4                   // ring depth in tiles
+#endif
+#ifndef SK_WGS_PER_CU
+#define SK_WGS_PER_CU 2            // workgroups per CU the register budget is sized for
+#endif
 #define SK_RESCALE_SLACK 8.0f
 
-__device__ __forceinline__ void sk_load_tile128(const sk_seg& g, int t0, int tid, uint4 (&kr)[4], uint4 (&vr)[4])
+typedef __attribute__((address_space(3))) void* sk_lds_ptr;
+typedef const __attribute__((address_space(1))) void* sk_glb_ptr;
+
+// s_waitcnt vmcnt(n) only (gfx9 encoding: vmcnt = simm16[3:0] | simm16[15:14] << 4)
+#define SK_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() would also wait for every
+// outstanding global load, i.e. drain the ring of tiles in flight.
+__device__ __forceinline__ void sk_lds_barrier()
 {
-    const int row = tid >> 4, cc = tid & 15;        // K: 16 lanes per 256-byte row
-    const int dd = tid >> 1, half = tid & 1;        // V^T: 2 lanes per 32-byte row of a group
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// One direct-to-LDS load of 16 bytes per lane: lane i's data lands at lds_addr + 16 i.
+// Written as inline assembly so that the compiler's automatic wait insertion does not drain the
+// tiles in flight before every LDS read; the waits are placed by hand (SK_WAIT_VMCNT).
+__device__ __forceinline__ void sk_dma16(const void* src, unsigned lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(src) : "memory", "m0");
+}
+
+// Pool blocks holding the two 16-key groups of the tile that starts at key t0 (scalar loads).
+// Groups past the end of the segment fall back to its last group.
+struct sk_tile_blocks { int32_t blk[2]; };
+__device__ __forceinline__ sk_tile_blocks sk_lookup_tile(const sk_seg& g, int t0, int last_group)
+{
+    typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+    sk_tile_blocks b;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int tg = t0 + 16 * i;
-        uint4 kx = make_uint4(0, 0, 0, 0), vx = make_uint4(0, 0, 0, 0);
-        if (tg < g.end) {
-            const unsigned char* bb = sk_group_base(g, tg);
-            const int slot0 = tg & (g.B - 1);
-            if (tg + row < g.end)
-                kx = *(const uint4*)(bb + (size_t)(slot0 + row) * 256 + cc * 16);
-            vx = *(const uint4*)(bb + g.v_off + (size_t)dd * (2 * g.B) + (slot0 + half * 8) * 2);
-            if (tg + 16 > g.end) {                   // ragged end: zero the keys past it
-                int valid = g.end - (tg + half * 8);
-                uint32_t wv[4] = {vx.x, vx.y, vx.z, vx.w};
+    for (int j = 0; j < 2; ++j) {
+        int tg = t0 + 16 * j;
+        tg = tg < last_group ? tg : last_group;
+        b.blk[j] = ((const_i32_ptr)(uintptr_t)g.table)[tg >> g.log2B];
+    }
+    return b;
+}
+
+// Issues the four direct-to-LDS loads with which this wave contributes to one tile.
+__device__ __forceinline__ void sk_issue_tile(const sk_seg& g, int t0, int last_group, const sk_tile_blocks& tb,
+                                              unsigned stage, int wave, int lane)
+{
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if (valid <= 2 * j) wv[j] = 0;
-                    else if (valid == 2 * j + 1) wv[j] &= 0xffffu;
-                }
-                vx = make_uint4(wv[0], wv[1], wv[2], wv[3]);
-            }
+    for (int j = 0; j < 2; ++j) {            // j = 16-key group of the tile
+        int tg = t0 + 16 * j;
+        tg = tg < last_group ? tg : last_group;
+        const unsigned char* bb = g.base + (int64_t)tb.blk[j] * g.blk_stride;
+        const int slot0 = tg & (g.B - 1);
+        // K: this wave fills LDS rows 16 j + 4 wave .. + 3; lane -> (row, chunk position)
+        {
+            const int rr = wave * 4 + (lane >> 4);          // row inside the group
+            const int c = (lane & 15) ^ rr;                 // source chunk for this position
+            const unsigned char* src = bb + (size_t)(slot0 + rr) * 256 + c * 16;
+            sk_dma16(src, stage + (j * 4 + wave) * 1024);
         }
-        kr[i] = kx; vr[i] = vx;
+        // V^T: this wave fills dims 32 wave .. + 31 of group j; lane -> (dim, half position)
+        {
+            const int dd = wave * 32 + (lane >> 1);
+            const int h = (lane & 1) ^ ((dd >> 3) & 1);
+            const unsigned char* src = bb + g.v_off + (size_t)dd * (2 * g.B) + (slot0 + h * 8) * 2;
+            sk_dma16(src, stage + 8192 + (j * 4 + wave) * 1024);
+        }
     }
 }
 
-__device__ __forceinline__ void sk_store_tile128(unsigned char* lds, int tid, const uint4 (&kr)[4], const uint4 (&vr)[4])
-{
-    const int row = tid >> 4, cc = tid & 15;
-    const int dd = tid >> 1, half = tid & 1;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        *(uint4*)(lds + (row + 16 * i) * 256 + ((cc ^ row) << 4)) = kr[i];
-        *(uint4*)(lds + 16384 + i * 4096 + dd * 32 + ((half ^ ((dd >> 3) & 1)) << 4)) = vr[i];
-    }
-}
+#ifdef SK_EXPERIMENT              // development builds: P.pad bit 0 = no arithmetic, bit 1 = no loads
+#define SK_EXP_LOADS if (!(P.pad & 2))
+#else
+#define SK_EXP_LOADS
+#endif
 
 template <int NPH>
-__global__ __launch_bounds__(256, 2) void sk_attn_bf16_d128(const sk_launch P)
+__global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk_launch P)
 {
     constexpr int NRG = 4 / NPH;
-    constexpr int TKP = SK_TK / NPH;     // keys per wave per tile
-    constexpr int NSUB = TKP / 32;
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2][32768];
+    constexpr int TPI = 2;                   // tiles per iteration (64 keys)
+    constexpr int TPW = TPI / NPH;           // tiles per wave per iteration
+    constexpr int NSS = SK_NST / TPI;        // ring depth in iterations
+    constexpr int LP = 4 * TPI;              // loads per wave per iteration
+    static_assert(SK_NST % TPI == 0 && NSS >= 2, "ring depth");
+    __shared__ __attribute__((aligned(16))) unsigned char lds[SK_NST * SK_TILE_BYTES];
 
     sk_work w;
     if (!sk_decode_work(P, blockIdx.x, w)) return;
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const unsigned lds_base = (unsigned)(uintptr_t)(sk_lds_ptr)lds;   // LDS byte address of the ring
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // in a scalar register
     const int rg = wave % NRG, ph = wave / NRG;
     const int r = lane & 31, kg = lane >> 5;
     const int log2G = P.g.log2G, G = P.g.G;
@@ -217,60 +282,113 @@ __global__ __launch_bounds__(256, 2) void sk_attn_bf16_d128(const sk_launch P)
     // key tau(rho): swap bits 2 and 3 of the S^T row index
     const int tau = (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1);
 
-    int it = 0;     // LDS buffer toggle, continues across segments
+#pragma unroll 1
     for (int s = 0; s < 3; ++s) {
-        if (s > 0 && w.eph_cnt[s - 1] <= 0) continue;
         sk_seg g = sk_make_seg(P, w, s);
         if (g.end <= g.begin) continue;
-        const int ntiles = (g.end - g.begin + SK_TK - 1) / SK_TK;
-        uint4 kr[4], vr[4];
-        sk_load_tile128(g, g.begin, tid, kr, vr);
-        for (int ti = 0; ti < ntiles; ++ti, ++it) {
-            unsigned char* buf = lds[it & 1];
-            sk_store_tile128(buf, tid, kr, vr);
-            const int t0 = g.begin + ti * SK_TK;
-            if (ti + 1 < ntiles) sk_load_tile128(g, t0 + SK_TK, tid, kr, vr);
-            __syncthreads();
+        const int ntiles = (g.end - g.begin + SK_TILE - 1) / SK_TILE;
+        const int niter = (ntiles + TPI - 1) / TPI;
+        const int last_group = (g.end - 1) & ~15;
+        const int seg_last_pos = g.end - 1 + g.pos_shift;
+        const int lim_wave_min = p_wave_min < seg_last_pos ? p_wave_min : seg_last_pos;
+        const int lim_wave_max = p_wave_max < seg_last_pos ? p_wave_max : seg_last_pos;
+        const int lim_row = p_row < seg_last_pos ? p_row : seg_last_pos;
 
-            // this wave's keys: tokens [tw, tw + TKP)
-            const int tw = t0 + ph * TKP;
-            const int seg_last_pos = g.end - 1 + g.pos_shift;
-            const int lim_wave_min = p_wave_min < seg_last_pos ? p_wave_min : seg_last_pos;
-            const int lim_wave_max = p_wave_max < seg_last_pos ? p_wave_max : seg_last_pos;
-            const int pos_first = tw + g.pos_shift;
-            if (!wave_has_rows || pos_first > lim_wave_max) continue;   // nothing visible here
-            const bool need_mask = pos_first + TKP - 1 > lim_wave_min;
-            const int lim_row = p_row < seg_last_pos ? p_row : seg_last_pos;
-
-            // S^T = K Q^T
-            f32x16 sacc[NSUB];
+        sk_lds_barrier();                      // ring free (previous segment fully consumed)
+        // prologue: iterations 0 .. NSS-2
 #pragma unroll
-            for (int sub = 0; sub < NSUB; ++sub) {
+        for (int pi = 0; pi < NSS - 1; ++pi) {
+            if (pi < niter) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) sacc[sub][v] = 0.f;
-                const int krow = ph * TKP + sub * 32 + tau;
-                const unsigned char* kp = buf + krow * 256;
-                const int sw = krow & 15;
-#pragma unroll
-                for (int ks = 0; ks < 8; ++ks) {
-                    uint4 a = *(const uint4*)(kp + (((ks * 2 + kg) ^ sw) << 4));
-                    sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), qreg[ks], sacc[sub], 0, 0, 0);
+                for (int p = 0; p < TPI; ++p) {
+                    const int t0 = g.begin + (pi * TPI + p) * SK_TILE;
+                    const sk_tile_blocks tb = sk_lookup_tile(g, t0, last_group);
+                    SK_EXP_LOADS sk_issue_tile(g, t0, last_group, tb, lds_base + ((pi % NSS) * TPI + p) * SK_TILE_BYTES, wave, lane);
                 }
             }
-            // scale to log2 units, mask, row maximum
-            float mt_ = SK_NEG_INF;
+        }
+        // block ids of the next refill are looked up one iteration ahead of their use
+        sk_tile_blocks nb[TPI];
 #pragma unroll
-            for (int sub = 0; sub < NSUB; ++sub) {
+        for (int p = 0; p < TPI; ++p)
+            nb[p] = sk_lookup_tile(g, g.begin + ((NSS - 1) * TPI + p) * SK_TILE, last_group);
+        // The query operand must have arrived before the loop (a wait for it placed by the
+        // compiler inside the loop would drain the ring on every iteration).
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    float x = sacc[sub][v] * c_scale;
-                    if (need_mask) {
-                        int pos = pos_first + sub * 32 + 16 * (v >> 3) + 8 * kg + (v & 7);
-                        x = (pos <= lim_row) ? x : SK_NEG_INF;
+        for (int ks = 0; ks < 8; ++ks) asm volatile("" : : "v"(qreg[ks]));
+        for (int it = 0; it < niter; ++it) {
+            // wait for this wave's loads of iteration `it`: at most min(NSS-2, niter-1-it)
+            // later iterations may stay outstanding
+            const int rem = niter - 1 - it;
+            if (NSS >= 4 && rem >= 2) SK_WAIT_VMCNT(2 * LP);
+            else if (NSS >= 3 && rem >= 1) SK_WAIT_VMCNT(1 * LP);
+            else SK_WAIT_VMCNT(0);
+            sk_lds_barrier();
+            // refill the stage consumed in iteration it-1 with iteration it+NSS-1 (its block
+            // ids were looked up during the previous iteration), then look up the next ones
+            {
+                const int ni = it + NSS - 1;
+                if (ni < niter) {
+#pragma unroll
+                    for (int p = 0; p < TPI; ++p)
+                        SK_EXP_LOADS sk_issue_tile(g, g.begin + (ni * TPI + p) * SK_TILE, last_group, nb[p],
+                                                   lds_base + ((ni % NSS) * TPI + p) * SK_TILE_BYTES, wave, lane);
+                    if (ni + 1 < niter) {
+#pragma unroll
+                        for (int p = 0; p < TPI; ++p)
+                            nb[p] = sk_lookup_tile(g, g.begin + ((ni + 1) * TPI + p) * SK_TILE, last_group);
                     }
-                    sacc[sub][v] = x;
-                    mt_ = fmaxf(mt_, x);
                 }
+            }
+
+            // this wave's TPW consecutive tiles of the iteration
+            const int tile0 = it * TPI + ph * TPW;
+            const unsigned char* buf = lds + ((it % NSS) * TPI + ph * TPW) * SK_TILE_BYTES;
+            const int pos_first = g.begin + tile0 * SK_TILE + g.pos_shift;
+            bool active = wave_has_rows && tile0 < ntiles && pos_first <= lim_wave_max;
+#ifdef SK_EXPERIMENT
+            if (P.pad & 1) active = false;      // stream only: no arithmetic
+#endif
+            if (!active) continue;
+            const bool need_mask = pos_first + TPW * SK_TILE - 1 > lim_wave_min;
+
+            // S^T = K Q^T, TPW independent accumulator chains
+            f32x16 sacc[TPW];
+#pragma unroll
+            for (int t = 0; t < TPW; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sacc[t][v] = 0.f;
+            {
+                const int sw = tau & 15;
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+                    for (int t = 0; t < TPW; ++t) {
+                        uint4 a = *(const uint4*)(buf + t * SK_TILE_BYTES + tau * 256 + (((ks * 2 + kg) ^ sw) << 4));
+                        sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), qreg[ks], sacc[t], 0, 0, 0);
+                    }
+            }
+            // scale to log2 units, mask (only tiles that cross a limit), row maximum
+            float mt_ = SK_NEG_INF;
+            if (need_mask) {
+#pragma unroll
+                for (int t = 0; t < TPW; ++t)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int pos = pos_first + t * SK_TILE + 16 * (v >> 3) + 8 * kg + (v & 7);
+                        const float x = (pos <= lim_row) ? sacc[t][v] * c_scale : SK_NEG_INF;
+                        sacc[t][v] = x;
+                        mt_ = fmaxf(mt_, x);
+                    }
+            } else {
+#pragma unroll
+                for (int t = 0; t < TPW; ++t)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const float x = sacc[t][v] * c_scale;
+                        sacc[t][v] = x;
+                        mt_ = fmaxf(mt_, x);
+                    }
             }
             mt_ = fmaxf(mt_, __shfl_xor(mt_, 32, 64));
             const bool raise = mt_ > m_ref + SK_RESCALE_SLACK;
@@ -285,27 +403,26 @@ __global__ __launch_bounds__(256, 2) void sk_attn_bf16_d128(const sk_launch P)
             }
             const float m_use = (m_ref == SK_NEG_INF) ? 0.f : m_ref;
             // P = exp2(x - m), row sums, O^T += V^T P^T
+            bf16x8 pb[TPW][2];
 #pragma unroll
-            for (int sub = 0; sub < NSUB; ++sub) {
-                bf16x8 pb[2];
+            for (int t = 0; t < TPW; ++t)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    float p = sk_exp2(sacc[sub][v] - m_use);
-                    l_run += p;
-                    pb[v >> 3][v & 7] = (__bf16)p;
+                for (int v = 0; v < 8; ++v) {
+                    const float p0 = sk_exp2(sacc[t][v] - m_use), p1 = sk_exp2(sacc[t][8 + v] - m_use);
+                    l_run += p0 + p1;
+                    pb[t][0][v] = (__bf16)p0;
+                    pb[t][1][v] = (__bf16)p1;
                 }
-                const int sb0 = (ph * TKP + sub * 32) >> 4;
 #pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    const unsigned char* vp = buf + 16384 + (sb0 + q) * 4096;
+            for (int t = 0; t < TPW; ++t)
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
 #pragma unroll
                     for (int mt = 0; mt < 4; ++mt) {
                         const int dd = mt * 32 + r;
-                        uint4 a = *(const uint4*)(vp + dd * 32 + ((kg ^ ((dd >> 3) & 1)) << 4));
-                        oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pb[q], oacc[mt], 0, 0, 0);
+                        uint4 a = *(const uint4*)(buf + t * SK_TILE_BYTES + 8192 + q * 4096 + dd * 32 + ((kg ^ ((dd >> 3) & 1)) << 4));
+                        oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pb[t][q], oacc[mt], 0, 0, 0);
                     }
-                }
-            }
         }
     }
 
@@ -314,7 +431,7 @@ __global__ __launch_bounds__(256, 2) void sk_attn_bf16_d128(const sk_launch P)
     if (NPH > 1) {
         // merge the key phases of each row group through LDS: [value index][lane], value 64 = m, 65 = l
         __syncthreads();
-        float* xch = (float*)&lds[0][0] + rg * (66 * 64);
+        float* xch = (float*)&lds[0] + rg * (66 * 64);
         if (ph == 1) {
 #pragma unroll
             for (int mt = 0; mt < 4; ++mt)
@@ -419,7 +536,6 @@ __global__ __launch_bounds__(256) void sk_attn_simple(const sk_launch P)
     float m_run = SK_NEG_INF, l_run = 0.f;
 
     for (int s = 0; s < 3; ++s) {
-        if (s > 0 && w.eph_cnt[s - 1] <= 0) continue;
         sk_seg g = sk_make_seg(P, w, s);
         for (int t0 = g.begin; t0 < g.end; t0 += 32) {
             __syncthreads();
@@ -532,22 +648,60 @@ __global__ __launch_bounds__(256) void sk_combine(const sk_launch P)
     if (row >= cb.n_tok * G) return;
     const int tok_local = row / G;
     const int hq = cb.kv_head * G + row % G;
+    const size_t prow0 = (size_t)cb.part0 * P.rows_per_slot + row;
+    const size_t pstride = (size_t)cb.part_stride * P.rows_per_slot;
+    // Lane s owns (m, l) of part base+s; rows are read in batches of eight parts, the next
+    // batch requested before the current one is used, so one memory latency covers the kernel.
+    const int per_lane = d >> 6;     // 1 (d=64) or 2 (d=128)
+    const float* obase = P.part_o + prow0 * d + per_lane * lane;
+    const size_t ostride = pstride * d;
     float M = SK_NEG_INF;
-    for (int s = 0; s < cb.n_parts; ++s) {
-        size_t prow = (size_t)(cb.part0 + s * cb.part_stride) * P.rows_per_slot + row;
-        M = fmaxf(M, P.part_ml[prow * 2]);
+    if (cb.n_parts > 64) {           // rare: the maximum needs its own pass
+        for (int s = lane; s < cb.n_parts; s += 64) M = fmaxf(M, P.part_ml[(prow0 + s * pstride) * 2]);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
     }
     float L = 0.f, a0 = 0.f, a1 = 0.f;
-    const int per_lane = d >> 6;     // 1 (d=64) or 2 (d=128)
-    for (int s = 0; s < cb.n_parts; ++s) {
-        size_t prow = (size_t)(cb.part0 + s * cb.part_stride) * P.rows_per_slot + row;
-        float2 ml = *(const float2*)(P.part_ml + prow * 2);
-        float wgt = (ml.x == SK_NEG_INF) ? 0.f : sk_exp2(ml.x - M);
+    for (int base = 0; base < cb.n_parts; base += 64) {
+        const int cnt = cb.n_parts - base < 64 ? cb.n_parts - base : 64;
+        float2 ml = make_float2(SK_NEG_INF, 0.f);
+        if (lane < cnt) ml = *(const float2*)(P.part_ml + (prow0 + (base + lane) * pstride) * 2);
+        float2 x[8], y[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            x[j] = make_float2(0.f, 0.f);
+            if (j < cnt) {
+                const float* op = obase + (size_t)(base + j) * ostride;
+                if (per_lane == 2) x[j] = *(const float2*)op; else x[j].x = *op;
+            }
+        }
+        if (cb.n_parts <= 64) {
+            M = ml.x;
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
+        }
+        const float wgt = (ml.x == SK_NEG_INF) ? 0.f : sk_exp2(ml.x - M);
         L += ml.y * wgt;
-        const float* op = P.part_o + prow * d;
-        if (per_lane == 2) { float2 x = *(const float2*)(op + 2 * lane); a0 += x.x * wgt; a1 += x.y * wgt; }
-        else a0 += op[lane] * wgt;
+        for (int j0 = 0; j0 < cnt; j0 += 8) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {           // request the next batch
+                y[j] = make_float2(0.f, 0.f);
+                if (j0 + 8 + j < cnt) {
+                    const float* op = obase + (size_t)(base + j0 + 8 + j) * ostride;
+                    if (per_lane == 2) y[j] = *(const float2*)op; else y[j].x = *op;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float wj = __shfl(wgt, j0 + j, 64);    // 0 for parts past the end
+                a0 += x[j].x * wj; a1 += x[j].y * wj;
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) x[j] = y[j];
+        }
     }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) L += __shfl_xor(L, off, 64);
     const float inv = 1.0f / L;
     const size_t orow = ((size_t)(cb.q_tok0 + tok_local) * P.g.Hq + hq);
     if (P.out_dtype == 0) {
@@ -601,21 +755,29 @@ __global__ __launch_bounds__(256) void sk_scatter_kernel(const sk_geom g, const 
             vt[row][t] = ((const uint16_t*)v)[((size_t)(it.src_tok0 + row) * g.Hkv + head) * d + t];
         }
         __syncthreads();
-        uint16_t* vd = (uint16_t*)(dst + v_off);
-        if (it.count == 16) {
-            // whole group: 2 lanes per dimension, 8 tokens (16 bytes) each
+        // Slots of the 16-token group behind the last committed token are zero-filled, so that a
+        // key the attention kernel masks out never multiplies 0 by leftover bits.
+        const int first = it.dst_slot0 & 15;            // position inside the 16-token group
+        uint16_t* vd = (uint16_t*)(dst + v_off) + (it.dst_slot0 - first);
+        if (first == 0) {
+            // from the start of the group: 2 lanes per dimension, 8 tokens (16 bytes) each
             for (int idx = tid; idx < 2 * d; idx += 256) {
                 const int t = idx >> 1, half = idx & 1;
                 uint32_t wv[4];
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    wv[j] = (uint32_t)vt[half * 8 + 2 * j][t] | ((uint32_t)vt[half * 8 + 2 * j + 1][t] << 16);
-                *(uint4*)(vd + (size_t)t * Bd + it.dst_slot0 + half * 8) = make_uint4(wv[0], wv[1], wv[2], wv[3]);
+                for (int j = 0; j < 4; ++j) {
+                    const int s0 = half * 8 + 2 * j;
+                    const uint32_t lo = s0 < it.count ? vt[s0][t] : 0u;
+                    const uint32_t hi = s0 + 1 < it.count ? vt[s0 + 1][t] : 0u;
+                    wv[j] = lo | (hi << 16);
+                }
+                *(uint4*)(vd + (size_t)t * Bd + half * 8) = make_uint4(wv[0], wv[1], wv[2], wv[3]);
             }
         } else {
-            for (int idx = tid; idx < it.count * d; idx += 256) {
-                const int t = idx / it.count, row = idx % it.count;
-                vd[(size_t)t * Bd + it.dst_slot0 + row] = vt[row][t];
+            const int span = 16 - first;                 // slots first..15: tokens, then zeros
+            for (int idx = tid; idx < span * d; idx += 256) {
+                const int t = idx / span, jj = idx % span;
+                vd[(size_t)t * Bd + first + jj] = jj < it.count ? vt[jj][t] : (uint16_t)0;
             }
         }
     }

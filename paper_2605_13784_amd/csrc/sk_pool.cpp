@@ -41,7 +41,7 @@ struct Layout {
     int64_t part_slots = 0;
     size_t kv_bytes = 0;
     // workspace offsets
-    size_t off_tables = 0, off_meta = 0, off_part_ml = 0, off_part_o = 0, off_eph = 0, ws_bytes = 0;
+    size_t off_tables = 0, off_ident = 0, off_meta = 0, off_part_ml = 0, off_part_o = 0, off_eph = 0, ws_bytes = 0;
 };
 
 bool derive_layout(const sk_pool_desc& d, Layout& L)
@@ -55,11 +55,13 @@ bool derive_layout(const sk_pool_desc& d, Layout& L)
     L.elem = d.dtype == SK_F32 ? 4 : 2;
     L.G = d.n_q_heads / d.n_kv_heads;
     L.v_off = int64_t(d.block_tokens) * d.head_dim * L.elem;
-    L.head_stride = 2 * L.v_off;
-    L.blk_stride = L.head_stride * d.n_kv_heads;
+    // [kv_head][block][K | V]: the blocks of one head are contiguous, so a workgroup (which
+    // streams one head) reads whole consecutive 8 KiB pieces when the table is in order
+    L.blk_stride = 2 * L.v_off;
+    L.head_stride = L.blk_stride * d.n_blocks;
     L.eph_v_off = int64_t(16) * d.head_dim * L.elem;
-    L.eph_head_stride = 2 * L.eph_v_off;
-    L.eph_blk_stride = L.eph_head_stride * d.n_kv_heads;
+    L.eph_blk_stride = 2 * L.eph_v_off;
+    L.eph_head_stride = 0;     // set once the number of staging blocks is known
     int64_t mst = d.max_session_tokens ? d.max_session_tokens : d.n_blocks * d.block_tokens;
     mst = std::min<int64_t>(mst, d.n_blocks * d.block_tokens);
     if (mst > (int64_t(1) << 29)) return false;       // positions are int32 with head room
@@ -68,15 +70,17 @@ bool derive_layout(const sk_pool_desc& d, Layout& L)
     L.max_batch_tokens = d.max_batch_tokens ? d.max_batch_tokens : 4096;
     if (L.max_batch_tokens > (1 << 20)) return false;
     L.eph_blocks = (L.max_batch_tokens + 15) / 16 + std::max(d.max_sessions, 1024) + 1;
+    L.eph_head_stride = L.eph_blk_stride * L.eph_blocks;
     int64_t rows = int64_t(L.max_batch_tokens) * d.n_q_heads;
     L.part_slots = 2048 + 2 * ((rows + kPartSlotRows - 1) / kPartSlotRows);
-    L.kv_bytes = size_t(L.blk_stride) * size_t(d.n_blocks);
+    L.kv_bytes = size_t(2 * L.v_off) * size_t(d.n_kv_heads) * size_t(d.n_blocks);
     size_t off = 0;
     L.off_tables = off; off = align_up(off + size_t(d.max_sessions) * L.max_blocks_per_session * 4, 256);
+    L.off_ident = off;  off = align_up(off + size_t(L.eph_blocks) * 4, 256);
     L.off_meta = off;   off = align_up(off + kMetaBytes, 256);
     L.off_part_ml = off; off = align_up(off + size_t(L.part_slots) * kPartSlotRows * 2 * 4, 256);
     L.off_part_o = off; off = align_up(off + size_t(L.part_slots) * kPartSlotRows * d.head_dim * 4, 256);
-    L.off_eph = off;    off = align_up(off + size_t(L.eph_blocks) * L.eph_blk_stride, 256);
+    L.off_eph = off;    off = align_up(off + size_t(L.eph_blocks) * L.eph_blk_stride * d.n_kv_heads, 256);
     L.ws_bytes = off;
     return true;
 }
@@ -233,6 +237,9 @@ int run_regular(sk_pool* p, int32_t id, const void* q, int64_t n_tok, int32_t po
     L.chunk = (int32_t)chunk;
     L.n_splits = (int32_t)parts;
     L.eph_blk[0] = 0; L.eph_cnt[0] = eph_cnt; L.eph_pos0[0] = eph_pos0;
+#ifdef SK_EXPERIMENT
+    if (const char* x = getenv("SK_EXPERIMENT")) L.pad = atoi(x);
+#endif
     const int32_t wgs = int32_t(base_wgs * parts);
     hipEvent_t* pe = prof_begin(p, st);
     int e = sk_launch_attention(L, v.id, wgs, st);
@@ -359,9 +366,10 @@ int sk_pool_create(const sk_pool_desc* desc, sk_pool** out)
     g.kv = (const unsigned char*)desc->kv_mem;
     g.eph = meta_only ? nullptr : (const unsigned char*)desc->workspace + L.off_eph;
     g.tables = meta_only ? nullptr : (const int32_t*)((const unsigned char*)desc->workspace + L.off_tables);
+    g.eph_ident = meta_only ? nullptr : (const int32_t*)((const unsigned char*)desc->workspace + L.off_ident);
     g.blk_stride = L.blk_stride; g.eph_blk_stride = L.eph_blk_stride;
-    g.head_stride = (int32_t)L.head_stride; g.v_off = (int32_t)L.v_off;
-    g.eph_head_stride = (int32_t)L.eph_head_stride; g.eph_v_off = (int32_t)L.eph_v_off;
+    g.head_stride = L.head_stride; g.v_off = (int32_t)L.v_off;
+    g.eph_head_stride = L.eph_head_stride; g.eph_v_off = (int32_t)L.eph_v_off;
     g.B = desc->block_tokens; g.log2B = ilog2_exact(desc->block_tokens);
     g.Hq = desc->n_q_heads; g.Hkv = desc->n_kv_heads; g.G = L.G; g.log2G = ilog2_exact(L.G);
     g.d = desc->head_dim; g.elem = L.elem;
@@ -374,6 +382,11 @@ int sk_pool_create(const sk_pool_desc* desc, sk_pool** out)
             e = hipEventCreateWithFlags(&p->ring_ev[i], hipEventDisableTiming);
             if (e != hipSuccess) { g_last_hip = (int)e; sk_pool_destroy(p); return SK_E_HIP; }
         }
+        // identity table over the staging blocks (one synchronous copy at creation)
+        std::vector<int32_t> ident((size_t)L.eph_blocks);
+        for (size_t i = 0; i < ident.size(); ++i) ident[i] = (int32_t)i;
+        e = hipMemcpy((unsigned char*)desc->workspace + L.off_ident, ident.data(), ident.size() * 4, hipMemcpyHostToDevice);
+        if (e != hipSuccess) { g_last_hip = (int)e; sk_pool_destroy(p); return SK_E_HIP; }
     }
     *out = p;
     return SK_OK;

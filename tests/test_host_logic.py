@@ -138,10 +138,10 @@ def test_session_limits():
 def test_element_offsets_describe_the_layout():
     p = meta_pool(n_blocks=4, block_tokens=16)
     e = 2
-    blk = 8 * 2 * 16 * 128 * e
+    blk = 2 * 16 * 128 * e                         # one (head, block): K then V
     assert p.sk_pool_element_offset(0, 0, False, 0, 0) == 0
     assert p.sk_pool_element_offset(1, 0, False, 0, 0) == blk
-    assert p.sk_pool_element_offset(0, 1, False, 0, 0) == 2 * 16 * 128 * e
+    assert p.sk_pool_element_offset(0, 1, False, 0, 0) == 4 * blk          # heads are outermost
     assert p.sk_pool_element_offset(0, 0, False, 3, 5) == (3 * 128 + 5) * e
     assert p.sk_pool_element_offset(0, 0, True, 3, 5) == 16 * 128 * e + (5 * 16 + 3) * e    # V is [dim][token]
     assert p.sk_pool_element_offset(4, 0, False, 0, 0) == -1
