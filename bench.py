@@ -100,6 +100,9 @@ def main():
     ap.add_argument("--hot", action="store_true", help="one session only: K/V may stay in the last-level cache")
     ap.add_argument("--n-splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy three times before the steps (a kernel of known "
+                         "size against which hardware byte counters are scaled)")
     ap.add_argument("--cpu-rows", type=int, default=0, help="oracle sample size in output rows (0: sized for ~15 s)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -137,6 +140,13 @@ def main():
         pool.sk_session_query(sid, qq, out=out_q, lse=lse_q, n_splits=args.n_splits)
         pool.sk_session_truncate(sid, n0)
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
