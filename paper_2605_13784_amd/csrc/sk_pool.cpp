@@ -321,6 +321,172 @@ int check_out_dtype(const sk_pool* p, int out_dtype)
     return SK_OK;
 }
 
+// ---- list mode: many row tiles (of several sessions, or of one question batch) in one launch ----
+
+struct TileReq {            // one tile of query rows and the keys it may see
+    int32_t tbl_off, q_tok0, n_tok;
+    int32_t pos0;           // absolute position of its first token, or SK_NO_CAUSAL
+    int32_t kv_vis;         // cached tokens visible to the tile (positions 0 .. kv_vis-1)
+    int32_t eph_blk[2], eph_cnt[2], eph_pos0[2];
+};
+struct ListGroup {          // tiles that share a kernel variant and the q/out/lse arrays
+    Variant v = {SK_KV_SIMPLE, 16, 1};
+    const void* q = nullptr; void* out = nullptr; float* lse = nullptr;
+    std::vector<TileReq> tiles;
+};
+struct ScatterBatch { const void* k = nullptr; const void* v = nullptr; std::vector<sk_scatter> items; };
+
+// Cuts T tokens (packed rows q_row0..) that share `base` into row tiles of the group's height.
+void add_tiles(ListGroup& g, const TileReq& base, int32_t q_row0, int32_t T)
+{
+    for (int32_t t0 = 0; t0 < T; t0 += g.v.tok_per_tile) {
+        TileReq r = base;
+        r.q_tok0 = q_row0 + t0;
+        r.n_tok = std::min(g.v.tok_per_tile, T - t0);
+        if (base.pos0 < SK_NO_CAUSAL) {
+            r.pos0 = base.pos0 + t0;
+            r.kv_vis = std::min<int64_t>(base.kv_vis, int64_t(r.pos0) + r.n_tok);
+        }
+        g.tiles.push_back(r);
+    }
+}
+
+int run_list(sk_pool* p, ScatterBatch* sb, int n_sb, ListGroup* groups, int n_groups, int out_dtype, hipStream_t st)
+{
+    const int Hkv = p->d.n_kv_heads;
+    int64_t kv_total = 0, n_tiles = 0;
+    for (int gi = 0; gi < n_groups; ++gi)
+        for (const TileReq& t : groups[gi].tiles) { kv_total += t.kv_vis; ++n_tiles; }
+    if (n_tiles == 0) return SK_OK;
+    // one chunk length for the whole step, so that workgroups cost about the same
+    const int64_t target = 4 * int64_t(p->target_wgs);
+    int64_t chunk = std::max<int64_t>(256, (kv_total * Hkv + target - 1) / target);
+    chunk = (chunk + 63) / 64 * 64;
+    const int64_t cap_rows = p->L.part_slots * kPartSlotRows;
+    std::vector<sk_work> work[2];
+    std::vector<sk_comb> comb[2];
+    int64_t rows_base[2] = {0, 0};
+    for (;;) {
+        int64_t rows_used = 0;
+        bool ok = true;
+        for (int gi = 0; gi < n_groups && ok; ++gi) {
+            ListGroup& g = groups[gi];
+            work[gi].clear(); comb[gi].clear();
+            rows_base[gi] = rows_used;
+            int64_t slot = 0;       // in units of this group's rows_per_slot, from rows_base
+            // runs of consecutive tiles of one session: split-major order inside a run, so that
+            // workgroups resident at the same time read the same keys (L2 reuse across row tiles)
+            size_t i0 = 0;
+            while (i0 < g.tiles.size()) {
+                size_t i1 = i0;
+                int32_t max_parts = 1;
+                std::vector<int32_t> nparts, slot0;
+                while (i1 < g.tiles.size() && g.tiles[i1].tbl_off == g.tiles[i0].tbl_off) {
+                    const int32_t np = std::max<int64_t>(1, (g.tiles[i1].kv_vis + chunk - 1) / chunk);
+                    nparts.push_back(np); max_parts = std::max(max_parts, np);
+                    slot0.push_back(np > 1 ? (int32_t)slot : -1);
+                    if (np > 1) slot += int64_t(np) * Hkv;
+                    ++i1;
+                }
+                for (int32_t part = 0; part < max_parts; ++part)
+                    for (size_t i = i0; i < i1; ++i) {
+                        const TileReq& t = g.tiles[i];
+                        const int32_t np = nparts[i - i0];
+                        if (part >= np) continue;
+                        for (int h = 0; h < Hkv; ++h) {
+                            sk_work w = {};
+                            w.tbl_off = t.tbl_off; w.kv_head = h; w.q_tok0 = t.q_tok0; w.n_tok = t.n_tok; w.pos0 = t.pos0;
+                            w.kv_begin = int32_t(part * chunk);
+                            w.kv_end = int32_t(std::min<int64_t>(t.kv_vis, (part + 1) * chunk));
+                            w.part = np > 1 ? slot0[i - i0] + part * Hkv + h : -1;
+                            if (part == np - 1)
+                                for (int e = 0; e < 2; ++e) { w.eph_blk[e] = t.eph_blk[e]; w.eph_cnt[e] = t.eph_cnt[e]; w.eph_pos0[e] = t.eph_pos0[e]; }
+                            work[gi].push_back(w);
+                        }
+                    }
+                for (size_t i = i0; i < i1; ++i) {
+                    if (nparts[i - i0] < 2) continue;
+                    for (int h = 0; h < Hkv; ++h) {
+                        sk_comb c = {};
+                        c.part0 = slot0[i - i0] + h; c.n_parts = nparts[i - i0]; c.part_stride = Hkv;
+                        c.q_tok0 = g.tiles[i].q_tok0; c.n_tok = g.tiles[i].n_tok; c.kv_head = h;
+                        comb[gi].push_back(c);
+                    }
+                }
+                i0 = i1;
+            }
+            rows_used += slot * g.v.rows_per_slot;
+            if (rows_used > cap_rows) ok = false;
+        }
+        size_t bytes = 0;
+        for (int i = 0; i < n_sb; ++i) bytes += align_up(sb[i].items.size() * sizeof(sk_scatter), 256);
+        for (int gi = 0; gi < n_groups; ++gi)
+            bytes += align_up(work[gi].size() * sizeof(sk_work), 256) + align_up(comb[gi].size() * sizeof(sk_comb), 256);
+        if (ok && bytes <= kMetaBytes) break;
+        if (chunk > (int64_t(1) << 30)) return SK_E_WORKSPACE;
+        chunk *= 2;
+    }
+    // one upload: scatter lists, work lists, combine lists
+    int slot; unsigned char* host;
+    int rc = ring_acquire(p, &slot, &host);
+    if (rc) return rc;
+    unsigned char* ws = (unsigned char*)p->d.workspace;
+    unsigned char* dev_meta = ws + p->L.off_meta;
+    size_t off = 0, off_sb[2] = {0, 0}, off_work[2] = {0, 0}, off_comb[2] = {0, 0};
+    for (int i = 0; i < n_sb; ++i) {
+        off_sb[i] = off;
+        memcpy(host + off, sb[i].items.data(), sb[i].items.size() * sizeof(sk_scatter));
+        off += align_up(sb[i].items.size() * sizeof(sk_scatter), 256);
+    }
+    for (int gi = 0; gi < n_groups; ++gi) {
+        off_work[gi] = off;
+        memcpy(host + off, work[gi].data(), work[gi].size() * sizeof(sk_work));
+        off += align_up(work[gi].size() * sizeof(sk_work), 256);
+        off_comb[gi] = off;
+        memcpy(host + off, comb[gi].data(), comb[gi].size() * sizeof(sk_comb));
+        off += align_up(comb[gi].size() * sizeof(sk_comb), 256);
+    }
+    rc = ring_upload(p, slot, off, st);
+    if (rc) return rc;
+    for (int i = 0; i < n_sb; ++i) {
+        if (sb[i].items.empty()) continue;
+        int e = sk_launch_scatter(p->geom, sb[i].k, sb[i].v, (const sk_scatter*)(dev_meta + off_sb[i]), (int32_t)sb[i].items.size(),
+                                  (int32_t*)(ws + p->L.off_tables), (unsigned char*)p->d.kv_mem, ws + p->L.off_eph, st);
+        if (e) { g_last_hip = e; return SK_E_HIP; }
+        p->stats.launches++;
+    }
+    hipEvent_t* pe = prof_begin(p, st);
+    sk_launch L[2];
+    int32_t wgs = 0, max_parts = 1;
+    for (int gi = 0; gi < n_groups; ++gi) {
+        if (work[gi].empty()) continue;
+        ListGroup& g = groups[gi];
+        fill_launch_common(p, L[gi], g.q, g.out, out_dtype, g.lse, g.v);
+        L[gi].mode = SK_MODE_LIST;
+        L[gi].part_ml += rows_base[gi] * 2;
+        L[gi].part_o += rows_base[gi] * p->d.head_dim;
+        L[gi].work = (const sk_work*)(dev_meta + off_work[gi]);
+        L[gi].comb = (const sk_comb*)(dev_meta + off_comb[gi]);
+        int e = sk_launch_attention(L[gi], g.v.id, (int32_t)work[gi].size(), st);
+        if (e) { g_last_hip = e; return SK_E_HIP; }
+        p->stats.launches++;
+        wgs += (int32_t)work[gi].size();
+        for (const sk_comb& c : comb[gi]) max_parts = std::max(max_parts, c.n_parts);
+    }
+    if (pe) (void)hipEventRecord(pe[1], st);
+    for (int gi = 0; gi < n_groups; ++gi) {
+        if (comb[gi].empty()) continue;
+        int e = sk_launch_combine(L[gi], (int32_t)comb[gi].size(), st);
+        if (e) { g_last_hip = e; return SK_E_HIP; }
+        p->stats.launches++;
+    }
+    if (pe) (void)hipEventRecord(pe[2], st);
+    p->stats.kv_bytes_streamed += kv_total * 2 * Hkv * p->d.head_dim * p->L.elem;
+    p->last.workgroups = wgs; p->last.n_splits = max_parts; p->last.row_tiles = (int32_t)n_tiles;
+    p->last.kernel_variant = groups[0].tiles.empty() ? groups[n_groups - 1].v.id : groups[0].v.id;
+    return SK_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -531,17 +697,141 @@ int sk_session_query(sk_pool* p, int32_t id, const void* q, const void* k, const
     return run_regular(p, id, q, nq, SK_NO_CAUSAL, s->len, 0, 0, out, out_dtype, lse, n_splits, st);
 }
 
-int sk_batch_step(sk_pool*, int32_t, const int32_t*, const int32_t*, const int32_t*, const void*, const void*,
-                  const void*, void*, int, float*, void*)
+int sk_batch_step(sk_pool* p, int32_t n_items, const int32_t* session_id, const int32_t* op, const int32_t* cu_tokens,
+                  const void* q, const void* k, const void* v, void* out, int out_dtype, float* lse, void* hip_stream)
 {
-    return SK_E_INVAL;   // implemented in a later change
+    if (!p || n_items < 0) return SK_E_INVAL;
+    if (n_items == 0) return SK_OK;
+    if (!session_id || !op || !cu_tokens) return SK_E_INVAL;
+    if (n_items > p->d.max_sessions) return SK_E_INVAL;        // sessions are distinct
+    if (cu_tokens[0] != 0) return SK_E_INVAL;
+    std::vector<char> seen((size_t)p->d.max_sessions, 0);
+    int64_t need_blocks = 0;
+    bool any_kv = false;
+    for (int i = 0; i < n_items; ++i) {
+        const Session* s = get_session(p, session_id[i]);
+        if (!s) return SK_E_BADSESSION;
+        if (seen[session_id[i]]) return SK_E_INVAL;
+        seen[session_id[i]] = 1;
+        const int64_t T = int64_t(cu_tokens[i + 1]) - cu_tokens[i];
+        if (T < 0) return SK_E_INVAL;
+        if (op[i] != SK_OP_APPEND && op[i] != SK_OP_QUERY_A && op[i] != SK_OP_QUERY_B) return SK_E_INVAL;
+        if (T == 0) continue;
+        if (op[i] == SK_OP_APPEND) {
+            if (s->len + T > p->L.max_session_tokens) return SK_E_NOMEM;
+            need_blocks += blocks_needed(p, s->len, T);
+        }
+        if (op[i] == SK_OP_QUERY_A && s->len == 0) return SK_E_EMPTY;
+        if (op[i] != SK_OP_QUERY_A) any_kv = true;
+    }
+    const int64_t total = cu_tokens[n_items];
+    if (total > p->L.max_batch_tokens) return SK_E_WORKSPACE;
+    if (need_blocks > (int64_t)p->free_blocks.size()) return SK_E_NOMEM;
+    if (p->device) {
+        if (!q || !out || (any_kv && (!k || !v))) return SK_E_INVAL;
+        if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse)) return SK_E_INVAL;
+        int rc = check_out_dtype(p, out_dtype);
+        if (rc) return rc;
+        Variant vv;
+        if (!pick_variant(p, 1, vv)) return SK_E_SHAPE;
+    }
+    // nothing below fails for lack of pool resources
+    ScatterBatch sb;
+    sb.k = k; sb.v = v;
+    ListGroup groups[2];
+    int64_t eph_cursor = 0;
+    for (int i = 0; i < n_items; ++i) {
+        Session* s = get_session(p, session_id[i]);
+        const int32_t T = cu_tokens[i + 1] - cu_tokens[i];
+        if (T == 0) continue;
+        const int32_t id = session_id[i];
+        const int64_t n = s->len;
+        const int32_t tbl_off = int32_t(int64_t(id) * p->L.max_blocks_per_session);
+        TileReq base = {};
+        base.tbl_off = tbl_off;
+        if (op[i] == SK_OP_APPEND) {
+            const int64_t first_new = (int64_t)s->blocks.size();
+            take_blocks(p, s, blocks_needed(p, n, T));
+            s->len = n + T;
+            p->stats.tokens_appended += T;
+            if (!p->device) continue;
+            build_scatter(p, s, id, n, cu_tokens[i], T, first_new, false, 0, sb.items);
+            base.pos0 = (int32_t)n; base.kv_vis = int32_t(n + T);
+        } else {
+            if (!p->device) continue;
+            p->stats.tokens_queried += T;
+            if (op[i] == SK_OP_QUERY_B) {
+                build_scatter(p, nullptr, id, 0, cu_tokens[i], T, 0, true, eph_cursor, sb.items);
+                base.pos0 = (int32_t)n; base.kv_vis = (int32_t)n;
+                base.eph_blk[0] = (int32_t)eph_cursor; base.eph_cnt[0] = T; base.eph_pos0[0] = (int32_t)n;
+                eph_cursor += (T + 15) / 16;
+            } else {
+                base.pos0 = SK_NO_CAUSAL; base.kv_vis = (int32_t)n;
+            }
+        }
+        Variant vv;
+        pick_variant(p, T, vv);
+        ListGroup& g = groups[vv.id == SK_KV_MFMA64 ? 1 : 0];
+        g.v = vv; g.q = q; g.out = out; g.lse = lse;
+        add_tiles(g, base, cu_tokens[i], T);
+    }
+    if (!p->device) return SK_OK;
+    return run_list(p, &sb, 1, groups, 2, out_dtype, (hipStream_t)hip_stream);
 }
 
-int sk_session_query_shared_prefix(sk_pool*, int32_t, const void*, const void*, const void*, int32_t,
-                                   const void*, const void*, const void*, int32_t, int32_t,
-                                   void*, void*, int, float*, float*, void*)
+int sk_session_query_shared_prefix(sk_pool* p, int32_t id, const void* qp, const void* kp, const void* vp, int32_t P,
+                                   const void* qs, const void* ks, const void* vs, int32_t NQ, int32_t Sfx,
+                                   void* out_prefix, void* out_suffix, int out_dtype,
+                                   float* lse_prefix, float* lse_suffix, void* hip_stream)
 {
-    return SK_E_INVAL;   // implemented in a later change
+    if (!p) return SK_E_INVAL;
+    Session* s = get_session(p, id);
+    if (!s) return SK_E_BADSESSION;
+    if (P < 0 || NQ < 0 || Sfx < 0) return SK_E_INVAL;
+    if (P == 0 && (NQ == 0 || Sfx == 0)) return SK_OK;
+    if (!p->device) return SK_E_NODEVICE;
+    if (P > 0 && (!qp || !kp || !vp || !out_prefix)) return SK_E_INVAL;
+    const bool has_sfx = NQ > 0 && Sfx > 0;
+    if (has_sfx && (!qs || !ks || !vs || !out_suffix)) return SK_E_INVAL;
+    if (!aligned16(qp) || !aligned16(kp) || !aligned16(vp) || !aligned16(qs) || !aligned16(ks) || !aligned16(vs) ||
+        !aligned16(out_prefix) || !aligned16(out_suffix) || !aligned16(lse_prefix) || !aligned16(lse_suffix)) return SK_E_INVAL;
+    int rc = check_out_dtype(p, out_dtype);
+    if (rc) return rc;
+    const int64_t total = int64_t(P) + (has_sfx ? int64_t(NQ) * Sfx : 0);
+    const int64_t sfx_blocks = (Sfx + 15) / 16, pre_blocks = (P + 15) / 16;
+    if (total > p->L.max_batch_tokens || pre_blocks + (has_sfx ? NQ * sfx_blocks : 0) > p->L.eph_blocks) return SK_E_WORKSPACE;
+    Variant vtest;
+    if (!pick_variant(p, 1, vtest)) return SK_E_SHAPE;
+    const int64_t n = s->len;
+    const int32_t tbl_off = int32_t(int64_t(id) * p->L.max_blocks_per_session);
+    p->stats.tokens_queried += total;
+    ScatterBatch sb[2];
+    ListGroup groups[2];
+    if (P > 0) {
+        sb[0].k = kp; sb[0].v = vp;
+        build_scatter(p, nullptr, id, 0, 0, P, 0, true, 0, sb[0].items);
+        TileReq base = {};
+        base.tbl_off = tbl_off; base.pos0 = (int32_t)n; base.kv_vis = (int32_t)n;
+        base.eph_blk[0] = 0; base.eph_cnt[0] = P; base.eph_pos0[0] = (int32_t)n;
+        pick_variant(p, P, groups[0].v);
+        groups[0].q = qp; groups[0].out = out_prefix; groups[0].lse = lse_prefix;
+        add_tiles(groups[0], base, 0, P);
+    }
+    if (has_sfx) {
+        sb[1].k = ks; sb[1].v = vs;
+        pick_variant(p, Sfx, groups[1].v);
+        groups[1].q = qs; groups[1].out = out_suffix; groups[1].lse = lse_suffix;
+        for (int32_t j = 0; j < NQ; ++j) {
+            const int64_t blk = pre_blocks + j * sfx_blocks;
+            build_scatter(p, nullptr, id, 0, j * Sfx, Sfx, 0, true, blk, sb[1].items);
+            TileReq base = {};
+            base.tbl_off = tbl_off; base.pos0 = int32_t(n + P); base.kv_vis = (int32_t)n;
+            base.eph_blk[0] = 0; base.eph_cnt[0] = P; base.eph_pos0[0] = (int32_t)n;
+            base.eph_blk[1] = (int32_t)blk; base.eph_cnt[1] = Sfx; base.eph_pos0[1] = int32_t(n + P);
+            add_tiles(groups[1], base, j * Sfx, Sfx);
+        }
+    }
+    return run_list(p, sb, 2, groups, 2, out_dtype, (hipStream_t)hip_stream);
 }
 
 int sk_session_gather(const sk_pool* p, int32_t id, int64_t first, int64_t count, void* k_out, void* v_out, void* hip_stream)
