@@ -1,0 +1,144 @@
+"""Properties the paper fixes for the stateful path, checked on the GPU:
+  I1  appending chunk by chunk == one causal pass over the whole stream (Sec. 2, Sec. 3.4);
+  I2  a query leaves the cache untouched (Sec. 3.3 Region 2; Sec. 3.9.3);
+  I3  a query does not depend on how the cache was built (Sec. 3.2 "complexity profile");
+  I4  Extend-then-Clear == a non-committing query with own K/V (Sec. 3.9.3);
+plus what this implementation promises on top: run-to-run determinism and independence of the
+physical block placement."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_13784_amd as sk
+from workloads import synth
+from gpu_common import Pair, compare, dev
+
+pytestmark = pytest.mark.gpu
+SHAPE = synth.CFG2
+
+
+def _stream(gen, T):
+    return synth.draw_qkv(gen, T, SHAPE)
+
+
+def test_chunking_history_does_not_matter():
+    """I1 + I3: three histories of the same 1,500-token stream give a bit-identical cache, outputs
+    within tolerance of the oracle for every token, a bit-identical query result and the same
+    launch geometry."""
+    gen = synth.generator(2, stream=10)
+    T = 1500
+    q, k, v = _stream(gen, T)
+    qq, kq, vq = _stream(gen, 32)
+    results = []
+    for cuts in ([0, 1500], [0, 256, 512, 768, 1024, 1280, 1500], [0, 1, 17, 300, 301, 900, 1499, 1500]):
+        pr = Pair(SHAPE, n_blocks=128, max_batch_tokens=2048)
+        sid = pr.create()
+        for a, b in zip(cuts[:-1], cuts[1:]):
+            pr.append(sid, q[a:b], k[a:b], v[a:b], name="append [%d,%d)" % (a, b))
+        pr.check_cache(sid)
+        kc, vc = pr.pool.sk_session_gather(sid)
+        oa, la = pr.query(sid, qq, name="query A")
+        geo_a = pr.pool.sk_pool_last_launch()
+        ob, lb = pr.query(sid, qq, kq, vq, name="query B")
+        torch.cuda.synchronize()
+        results.append((kc.cpu(), vc.cpu(), oa.cpu(), la.cpu(), ob.cpu(), lb.cpu(), geo_a))
+    for r in results[1:]:
+        for x, y in zip(r[:6], results[0][:6]):
+            assert torch.equal(x, y)
+        assert r[6] == results[0][6]
+
+
+def test_query_is_pure_and_deterministic():
+    """I2 + determinism: kv_mem, tables and lengths are unchanged by queries of both kinds and by a
+    question batch; the same call twice gives the same bits."""
+    gen = synth.generator(2, stream=11)
+    pr = Pair(SHAPE, n_blocks=200, max_sessions=2)
+    a, b = pr.create(), pr.create()
+    for sid, T in ((a, 1111), (b, 700)):
+        q, k, v = _stream(gen, T)
+        pr.append(sid, q, k, v, check=False)
+    torch.cuda.synchronize()
+    mem0 = pr.pool.kv_mem.clone()
+    tab0 = [pr.pool.sk_session_block_table(s) for s in (a, b)]
+    qq, kq, vq = (dev(t) for t in _stream(gen, 48))
+    outs = []
+    for rep in range(2):
+        o1, l1 = pr.pool.sk_session_query(a, qq)
+        o2, l2 = pr.pool.sk_session_query(a, qq, kq, vq, n_splits=3)
+        o3 = pr.pool.sk_session_query_shared_prefix(a, qq[:16], kq[:16], vq[:16], qq[16:].reshape(4, 8, 32, 128),
+                                                    kq[16:].reshape(4, 8, 8, 128), vq[16:].reshape(4, 8, 8, 128))
+        torch.cuda.synchronize()
+        outs.append([t.clone() for t in (o1, l1, o2, l2, o3[0], o3[2])])
+    for x, y in zip(outs[0], outs[1]):
+        assert torch.equal(x, y)
+    assert torch.equal(mem0, pr.pool.kv_mem)
+    assert tab0 == [pr.pool.sk_session_block_table(s) for s in (a, b)]
+    assert [pr.pool.sk_session_length(s) for s in (a, b)] == [1111, 700]
+
+
+def test_physical_block_placement_does_not_matter():
+    """Same logical cache, blocks handed out in order vs in a seeded random order: identical bits out."""
+    gen = synth.generator(2, stream=12)
+    q, k, v = _stream(gen, 2000)
+    qq, kq, vq = _stream(gen, 40)
+    res = []
+    for perm in (None, synth.permutation(synth.generator(2, stream=13), 160)):
+        pr = Pair(SHAPE, n_blocks=160, alloc_perm=perm, max_batch_tokens=2048)
+        sid = pr.create()
+        o1, l1 = pr.append(sid, q[:900], k[:900], v[:900])
+        o2, l2 = pr.append(sid, q[900:], k[900:], v[900:])
+        o3, l3 = pr.query(sid, qq, n_splits=4)
+        o4, l4 = pr.query(sid, qq, kq, vq)
+        torch.cuda.synchronize()
+        res.append([t.cpu() for t in (o1, l1, o2, l2, o3, l3, o4, l4)])
+        if perm is not None:
+            assert pr.pool.sk_session_block_table(sid) != sorted(pr.pool.sk_session_block_table(sid))
+    for x, y in zip(*res):
+        assert torch.equal(x, y)
+
+
+def test_extend_then_clear_equals_noncommitting_query():
+    """I4: append the question tokens, read the output, SeqRemove them (truncate) - the paper's literal
+    cycle - against the query that never commits.  Outputs agree (different tile alignment, so within
+    a tight tolerance rather than bit for bit) and the cache is back to its bytes."""
+    gen = synth.generator(2, stream=14)
+    pr = Pair(SHAPE, n_blocks=100)
+    sid = pr.create()
+    q, k, v = _stream(gen, 1000)
+    pr.append(sid, q, k, v, check=False)
+    qq, kq, vq = _stream(gen, 24)
+    ob, lb = pr.query(sid, qq, kq, vq, name="non-committing")
+    k0, v0 = pr.pool.sk_session_gather(sid)
+    free0 = pr.pool.sk_pool_blocks_free()
+    oa, la = pr.pool.sk_session_append(sid, dev(qq), dev(kq), dev(vq))
+    assert pr.pool.sk_session_length(sid) == 1024
+    pr.pool.sk_session_truncate(sid, 1000)
+    k1, v1 = pr.pool.sk_session_gather(sid)
+    torch.cuda.synchronize()
+    assert pr.pool.sk_session_length(sid) == 1000 and pr.pool.sk_pool_blocks_free() == free0
+    assert torch.equal(k0, k1) and torch.equal(v0, v1)
+    assert float((oa - ob).abs().max()) <= 2e-3 and float((la - lb).abs().max()) <= 1e-4
+    # the session keeps working after the truncate: next append lands on the same positions
+    q2, k2, v2 = _stream(gen, 50)
+    pr.append(sid, q2, k2, v2, name="append after truncate")
+    pr.check_cache(sid)
+
+
+def test_latency_scales_with_bytes_not_with_history():
+    """Not a timing test: the work the library launches for a query is a function of (n, |q|, splits)
+    only - same workgroups, same splits - whether the cache came from 2 or from 40 appends."""
+    gen = synth.generator(2, stream=15)
+    geos = []
+    for pieces in (2, 40):
+        pr = Pair(SHAPE, n_blocks=300, max_batch_tokens=4096)
+        sid = pr.create()
+        _, k, v = _stream(gen, 4000)
+        step = 4000 // pieces
+        for a in range(0, 4000, step):
+            pr.pool.sk_session_append(sid, None, dev(k[a:a + step]), dev(v[a:a + step]))
+        qq = dev(synth.draw(gen, (32, 32, 128), "bf16"))
+        pr.pool.sk_session_query(sid, qq)
+        geos.append(pr.pool.sk_pool_last_launch())
+        st = pr.pool.sk_pool_get_stats()
+        assert st["tokens_appended"] == 4000 and st["tokens_queried"] == 32
+    assert geos[0] == geos[1]
