@@ -360,14 +360,32 @@ __global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk
                 for (int v = 0; v < 16; ++v) sacc[t][v] = 0.f;
             {
                 const int sw = tau & 15;
+                uint4 ka[TPW][8];
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
-                    for (int t = 0; t < TPW; ++t) {
-                        uint4 a = *(const uint4*)(buf + t * SK_TILE_BYTES + tau * 256 + (((ks * 2 + kg) ^ sw) << 4));
-                        sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), qreg[ks], sacc[t], 0, 0, 0);
-                    }
+                    for (int t = 0; t < TPW; ++t)
+                        ka[t][ks] = *(const uint4*)(buf + t * SK_TILE_BYTES + tau * 256 + (((ks * 2 + kg) ^ sw) << 4));
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+                    for (int t = 0; t < TPW; ++t)
+                        sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[t][ks]), qreg[ks], sacc[t], 0, 0, 0);
+                // all LDS reads first, then the MFMAs back to back (two independent chains)
+                __builtin_amdgcn_sched_group_barrier(0x100, 8 * TPW, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 8 * TPW, 0);
             }
+            // V^T operands are requested now, so that their LDS latency hides behind the softmax
+            uint4 va[TPW][2][4];
+#pragma unroll
+            for (int t = 0; t < TPW; ++t)
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
+#pragma unroll
+                    for (int mt = 0; mt < 4; ++mt) {
+                        const int dd = mt * 32 + r;
+                        va[t][q][mt] = *(const uint4*)(buf + t * SK_TILE_BYTES + 8192 + q * 4096 + dd * 32 + ((kg ^ ((dd >> 3) & 1)) << 4));
+                    }
             // scale to log2 units, mask (only tiles that cross a limit), row maximum
             float mt_ = SK_NEG_INF;
             if (need_mask) {
@@ -418,11 +436,8 @@ __global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk
 #pragma unroll
                 for (int q = 0; q < 2; ++q)
 #pragma unroll
-                    for (int mt = 0; mt < 4; ++mt) {
-                        const int dd = mt * 32 + r;
-                        uint4 a = *(const uint4*)(buf + t * SK_TILE_BYTES + 8192 + q * 4096 + dd * 32 + ((kg ^ ((dd >> 3) & 1)) << 4));
-                        oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pb[t][q], oacc[mt], 0, 0, 0);
-                    }
+                    for (int mt = 0; mt < 4; ++mt)
+                        oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[t][q][mt]), pb[t][q], oacc[mt], 0, 0, 0);
         }
     }
 

@@ -104,6 +104,7 @@ struct sk_pool {
     sk_pool_stats stats = {};
     sk_launch_info last = {};
     int target_wgs = kDefaultTargetWgs;
+    bool target_wgs_set = false;         // overridden through the environment (tuning sweeps)
     // optional kernel timing
     bool profiling = false;
     std::vector<hipEvent_t> prof_ev;     // triples: before attention, after attention, after combine
@@ -220,7 +221,13 @@ int run_regular(sk_pool* p, int32_t id, const void* q, int64_t n_tok, int32_t po
     const int has_eph = eph_cnt > 0 ? 1 : 0;
     int64_t S;
     if (n_splits_req > 0) S = n_splits_req;
-    else S = std::max<int64_t>(1, (p->target_wgs + base_wgs / 2) / base_wgs);
+    else {
+        // A call with few row tiles (a query) is bound by streaming the cache once: one workgroup
+        // per CU measured faster than two (fewer split partials to write and merge).  Calls with
+        // many row tiles (appends) are bound by arithmetic and want two workgroups per CU.
+        const int64_t target = p->target_wgs_set ? p->target_wgs : (L.n_tiles <= 2 ? 256 : 512);
+        S = std::max<int64_t>(1, (target + base_wgs / 2) / base_wgs);
+    }
     int64_t chunk = kv_len > 0 ? (kv_len + S - 1) / S : 64;
     if (n_splits_req <= 0) chunk = std::max<int64_t>(chunk, 256);    // at least four key tiles per workgroup
     chunk = (chunk + 63) / 64 * 64;
@@ -540,7 +547,7 @@ int sk_pool_create(const sk_pool_desc* desc, sk_pool** out)
     g.Hq = desc->n_q_heads; g.Hkv = desc->n_kv_heads; g.G = L.G; g.log2G = ilog2_exact(L.G);
     g.d = desc->head_dim; g.elem = L.elem;
     g.scale_log2e = scale * 1.4426950408889634f;
-    if (const char* t = getenv("SK_TARGET_WGS")) { int x = atoi(t); if (x > 0) p->target_wgs = x; }
+    if (const char* t = getenv("SK_TARGET_WGS")) { int x = atoi(t); if (x > 0) { p->target_wgs = x; p->target_wgs_set = true; } }
     if (!meta_only) {
         hipError_t e = hipHostMalloc((void**)&p->ring, kMetaBytes * kRingSlots, hipHostMallocDefault);
         if (e != hipSuccess) { g_last_hip = (int)e; delete p; return SK_E_HIP; }
