@@ -238,6 +238,9 @@ __global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk
     sk_work w;
     if (!sk_decode_work(P, blockIdx.x, w)) return;
 
+#ifdef SK_EXPERIMENT
+    if (P.pad & 4) return;                     // launch overhead only
+#endif
     const unsigned lds_base = (unsigned)(uintptr_t)(sk_lds_ptr)lds;   // LDS byte address of the ring
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // in a scalar register
@@ -469,42 +472,49 @@ __global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk
         m_ref = M;
     }
 
-    if (!row_valid) return;
-    if (w.part < 0) {
-        const float inv = 1.0f / l_tot;
-        const size_t orow = ((size_t)(w.q_tok0 + tok_local) * P.g.Hq + hq);
-        if (P.out_dtype == 0) {
-            float* op = (float*)P.out + orow * 128;
+    // ---- epilogue: rows go out through LDS so that every store instruction writes whole rows ----
+    // A lane holds 4-float pieces of ONE row (its accumulators are O^T); written as they are, a store
+    // instruction would touch 64 different 128-byte lines.  Each wave transposes its 32 x 128 tile in
+    // its own 16 KiB of the (now idle) ring, XOR-swizzled by row so both directions are conflict-free.
+    if (NPH == 1) __syncthreads();                    // every wave is done reading key tiles
+#ifdef SK_EXPERIMENT
+    if (P.pad & 8) return;                     // no output
+#endif
+    const bool direct = w.part < 0;
+    const float inv = direct ? 1.0f / l_tot : 1.0f;
+    float* tr = (float*)lds + (NPH == 1 ? wave : rg * 2) * 4096;
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
+    for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    float4 o = make_float4(oacc[mt][q4 * 4 + 0] * inv, oacc[mt][q4 * 4 + 1] * inv,
-                                           oacc[mt][q4 * 4 + 2] * inv, oacc[mt][q4 * 4 + 3] * inv);
-                    *(float4*)(op + mt * 32 + q4 * 8 + kg * 4) = o;
-                }
-        } else {
-            uint16_t* op = (uint16_t*)P.out + orow * 128;
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    uint32_t lo = f32_to_bf16_bits(oacc[mt][q4 * 4 + 0] * inv) | ((uint32_t)f32_to_bf16_bits(oacc[mt][q4 * 4 + 1] * inv) << 16);
-                    uint32_t hi = f32_to_bf16_bits(oacc[mt][q4 * 4 + 2] * inv) | ((uint32_t)f32_to_bf16_bits(oacc[mt][q4 * 4 + 3] * inv) << 16);
-                    *(uint2*)(op + mt * 32 + q4 * 8 + kg * 4) = make_uint2(lo, hi);
-                }
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const int c4 = mt * 8 + q4 * 2 + kg;
+            *(float4*)(tr + r * 128 + ((c4 ^ r) & 31) * 4) =
+                make_float4(oacc[mt][q4 * 4 + 0] * inv, oacc[mt][q4 * 4 + 1] * inv, oacc[mt][q4 * 4 + 2] * inv, oacc[mt][q4 * 4 + 3] * inv);
         }
-        if (P.lse && kg == 0) P.lse[orow] = (m_ref + sk_log2(l_tot)) * SK_LN2;
-    } else {
-        const size_t prow = (size_t)w.part * P.rows_per_slot + row_in_tile;
-        float* op = P.part_o + prow * 128;
+    const size_t orow_lane = ((size_t)(w.q_tok0 + tok_local) * P.g.Hq + hq);
+    if (row_valid && kg == 0) {
+        if (direct) { if (P.lse) P.lse[orow_lane] = (m_ref + sk_log2(l_tot)) * SK_LN2; }
+        else *(float2*)(P.part_ml + ((size_t)w.part * P.rows_per_slot + row_in_tile) * 2) = make_float2(m_ref, l_tot);
+    }
+    const int c4 = lane & 31;
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4)
-                *(float4*)(op + mt * 32 + q4 * 8 + kg * 4) =
-                    make_float4(oacc[mt][q4 * 4 + 0], oacc[mt][q4 * 4 + 1], oacc[mt][q4 * 4 + 2], oacc[mt][q4 * 4 + 3]);
-        if (kg == 0) *(float2*)(P.part_ml + prow * 2) = make_float2(m_ref, l_tot);
+    for (int it = 0; it < 16; ++it) {
+        const int row = it * 2 + (lane >> 5);
+        const float4 val = *(const float4*)(tr + row * 128 + ((c4 ^ row) & 31) * 4);
+        const int rit = rg * 32 + row;                 // row inside the tile
+        const int tok2 = rit >> log2G;
+        if (tok2 >= w.n_tok) continue;
+        if (direct) {
+            const size_t orow = ((size_t)(w.q_tok0 + tok2) * P.g.Hq + w.kv_head * G + (rit & (G - 1)));
+            if (P.out_dtype == 0) *(float4*)((float*)P.out + orow * 128 + c4 * 4) = val;
+            else {
+                const uint32_t lo = f32_to_bf16_bits(val.x) | ((uint32_t)f32_to_bf16_bits(val.y) << 16);
+                const uint32_t hi = f32_to_bf16_bits(val.z) | ((uint32_t)f32_to_bf16_bits(val.w) << 16);
+                *(uint2*)((uint16_t*)P.out + orow * 128 + c4 * 4) = make_uint2(lo, hi);
+            }
+        } else {
+            *(float4*)(P.part_o + ((size_t)w.part * P.rows_per_slot + rit) * 128 + c4 * 4) = val;
+        }
     }
 }
 
