@@ -30,6 +30,11 @@ from workloads import synth  # noqa: E402
 HBM_PEAK_GBPS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
+# HBM bytes per dispatch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (fetch + write),
+# scaled by a 1 GiB device copy; see profiles/bench_cfg2_attention_kernels.md for the runs.
+# Keyed by (workload, block_tokens, cache state); other configurations report null.
+MEASURED_HBM_TRAFFIC = {}
+
 WORKLOADS = {
     # name: (shape, cached tokens at query time, append chunk, query tokens)
     "cfg2_llama3_8b_layer_32k": (synth.CFG2, 32768, 256, 32),
@@ -100,6 +105,7 @@ def main():
     ap.add_argument("--hot", action="store_true", help="one session only: K/V may stay in the last-level cache")
     ap.add_argument("--n-splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the other workloads (128K context, question batch, multi-tenant step)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy three times before the steps (a kernel of known "
                          "size against which hardware byte counters are scaled)")
@@ -115,7 +121,37 @@ def main():
 
     import paper_2605_13784_amd as sk
 
+    main_res = stream_workload(sk, args.workload, args, args.steps, args.warmup, calibrate=args.copy_calibration)
     shape, n, L, nq = WORKLOADS[args.workload]
+    res = {
+        "metric": "stream-step throughput: %d-token append + %d-token query at %d cached tokens" % (L, nq, n),
+        "value": main_res["tokens_per_s"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": main_res["config"], "query": main_res["query"], "append": main_res["append"],
+        "roofline": main_res["roofline"], "roofline_query": main_res["roofline_query"],
+        "roofline_append": main_res["roofline_append"],
+    }
+    if not args.no_extras:
+        extras = {}
+        other = "cfg3_long_context_128k" if "cfg2" in args.workload else "cfg2_llama3_8b_layer_32k"
+        r = stream_workload(sk, other, args, max(10, args.steps // 2), 4)
+        extras[other] = {k: r[k] for k in ("ms_per_step", "query", "append", "roofline_query", "roofline_append")}
+        extras["cfg5_question_batch_64k"] = question_batch(sk)
+        extras["cfg4_multi_tenant_step"] = multi_tenant(sk)
+        res["extras"] = extras
+    if not args.no_cpu_baseline:
+        rows = args.cpu_rows or ((L + nq) * shape.n_q_heads if n <= 32768 else 4096)
+        res["cpu_baseline"] = cpu_baseline(shape, n, L, nq, synth.generator(7), rows)
+    else:
+        res["cpu_baseline"] = None
+    print(json.dumps(res))
+
+
+def stream_workload(sk, name, args, steps, warmup, calibrate=False):
+    """Times `steps` stream steps (append + query + truncate back) of one workload, then the same
+    steps again with the library's HIP-event timing of the kernels switched on."""
+    shape, n, L, nq = WORKLOADS[name]
     B = args.block_tokens
     kv_per_session = n * shape.kv_bytes_per_token
     n_sessions = 1 if args.hot else (args.sessions or max(5, -(-(1 << 30) // kv_per_session) + 1))
@@ -124,9 +160,9 @@ def main():
     n_blocks = n_sessions * blocks_per_session + 4 * (L // B + 2)
     pool = sk.Pool(shape.dtype, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, B, n_blocks,
                    max_sessions=n_sessions, max_batch_tokens=max(L, nq, 1024))
-    gen = synth.generator(2 if "cfg2" in args.workload else 3)
+    gen = synth.generator(2 if "cfg2" in name else 3)
     n0 = n - L
-    sids = build_sessions(pool, shape, n0, L, n_sessions, gen)
+    sids = build_sessions(pool, shape, n0, 1024, n_sessions, gen)
     qa, ka, va = [t.cuda() for t in synth.draw_qkv(gen, L, shape)]
     qq = synth.draw(gen, (nq, shape.n_q_heads, shape.head_dim), shape.dtype).cuda()
     out_a = torch.empty((L, shape.n_q_heads, shape.head_dim), dtype=torch.float32, device="cuda")
@@ -140,34 +176,34 @@ def main():
         pool.sk_session_query(sid, qq, out=out_q, lse=lse_q, n_splits=args.n_splits)
         pool.sk_session_truncate(sid, n0)
 
-    if args.copy_calibration:
+    if calibrate:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i)
+    for i in range(steps):
+        step(warmup + i)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
 
     # same steps again with HIP events around the kernels (recorded by the library on the
     # stream the kernels run on)
     pool.sk_pool_set_profiling(True)
-    for i in range(args.steps):
-        step(args.warmup + args.steps + i)
+    for i in range(steps):
+        step(warmup + steps + i)
     torch.cuda.synchronize()
     _, attn_ms, comb_ms = pool.sk_pool_read_profile()
     pool.sk_pool_set_profiling(False)
     app_attn = np.array(attn_ms[0::2]); app_comb = np.array(comb_ms[0::2])
     qry_attn = np.array(attn_ms[1::2]); qry_comb = np.array(comb_ms[1::2])
     info = pool.sk_pool_last_launch()
+    pool.close()
 
     qb = query_bytes(shape, n, nq, B)
     af = append_flops(shape, n0, L)
@@ -175,22 +211,18 @@ def main():
     q_total_us = float((qry_attn + qry_comb).mean() * 1e3)
     a_kernel_us = float(app_attn.mean() * 1e3)
     a_total_us = float((app_attn + app_comb).mean() * 1e3)
+    traffic = MEASURED_HBM_TRAFFIC.get((name, B, "cold" if not args.hot else "hot"), {})
     roof_q = {"kernel": "sk_attn_bf16_d128 (query, split-KV partial)", "bound": "hbm",
               "achieved": qb / (q_kernel_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-              "frac": qb / (q_kernel_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, "traffic": None,
+              "frac": qb / (q_kernel_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, "traffic": traffic.get("query"),
               "avg_kernel_us": q_kernel_us, "algorithmic_bytes": qb}
     roof_a = {"kernel": "sk_attn_bf16_d128 (append, causal over cache + chunk)", "bound": "mfma",
               "achieved": af / (a_kernel_us * 1e-6) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-              "frac": af / (a_kernel_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+              "frac": af / (a_kernel_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic.get("append"),
               "avg_kernel_us": a_kernel_us, "algorithmic_flops": af}
-    dominant = roof_a if a_kernel_us >= q_kernel_us else roof_q
-
-    res = {
-        "metric": "stream-step throughput: %d-token append + %d-token query at %d cached tokens" % (L, nq, n),
-        "value": (L + nq) * args.steps / wall, "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": args.workload, "n_q_heads": shape.n_q_heads, "n_kv_heads": shape.n_kv_heads,
+    return {
+        "tokens_per_s": (L + nq) * steps / wall, "ms_per_step": wall * 1e3 / steps,
+        "config": {"workload": name, "n_q_heads": shape.n_q_heads, "n_kv_heads": shape.n_kv_heads,
                    "head_dim": shape.head_dim, "cached_tokens": n, "append_tokens": L, "query_tokens": nq,
                    "block_tokens": B, "sessions_rotated": n_sessions, "cache": "hot" if args.hot else "cold",
                    "query_splits": info["n_splits"], "query_workgroups": info["workgroups"]},
@@ -199,14 +231,101 @@ def main():
                   "p50_us": float(np.median(qry_attn + qry_comb) * 1e3), "max_us": float((qry_attn + qry_comb).max() * 1e3)},
         "append": {"latency_us": a_total_us, "kernel_us": a_kernel_us, "tokens_per_s": L / (a_total_us * 1e-6),
                    "tflops": af / (a_total_us * 1e-6) / 1e12, "mfma_frac": af / (a_total_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
-        "roofline": dominant, "roofline_query": roof_q, "roofline_append": roof_a,
+        "roofline": roof_a if a_kernel_us >= q_kernel_us else roof_q, "roofline_query": roof_q, "roofline_append": roof_a,
     }
-    if not args.no_cpu_baseline:
-        rows = args.cpu_rows or (1024 if n <= 32768 else 256)
-        res["cpu_baseline"] = cpu_baseline(shape, n, L, nq, synth.generator(7), rows)
-    else:
-        res["cpu_baseline"] = None
-    print(json.dumps(res))
+
+
+def question_batch(sk, n=65536, L=256, P=16, NQ=64, Sfx=8, cycles=8):
+    """Registered-question cycle at the 70B-layer shape: 256-token append, then 64 questions of
+    16 shared + 8 own tokens in one batched pass; also the same questions as 64 separate queries."""
+    shape = synth.CFG5
+    gen = synth.generator(5)
+    pool = sk.Pool(shape.dtype, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, 16, (n + L * (cycles + 2)) // 16 + 8,
+                   max_sessions=1, max_batch_tokens=1024)
+    sid = build_sessions(pool, shape, n - L, 1024, 1, gen)[0]
+    qa, ka, va = [t.cuda() for t in synth.draw_qkv(gen, L, shape)]
+    qp, kp, vp = [t.cuda() for t in synth.draw_qkv(gen, P, shape)]
+    qs, ks, vs = [t.cuda() for t in synth.draw_qkv(gen, NQ * Sfx, shape)]
+    r4 = lambda t: t.reshape(NQ, Sfx, t.shape[1], shape.head_dim)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3 * (cycles + 1))]
+    for c in range(cycles + 1):                         # first cycle is warm-up
+        ev[3 * c].record()
+        pool.sk_session_append(sid, qa, ka, va)
+        ev[3 * c + 1].record()
+        pool.sk_session_query_shared_prefix(sid, qp, kp, vp, r4(qs), r4(ks), r4(vs))
+        ev[3 * c + 2].record()
+    torch.cuda.synchronize()
+    app = [ev[3 * c].elapsed_time(ev[3 * c + 1]) for c in range(1, cycles + 1)]
+    bat = [ev[3 * c + 1].elapsed_time(ev[3 * c + 2]) for c in range(1, cycles + 1)]
+    n_end = pool.sk_session_length(sid)
+    qfull = torch.cat([qp.expand(1, -1, -1, -1).repeat(NQ, 1, 1, 1), r4(qs)], dim=1).contiguous()
+    kfull = torch.cat([kp.expand(1, -1, -1, -1).repeat(NQ, 1, 1, 1), r4(ks)], dim=1).contiguous()
+    vfull = torch.cat([vp.expand(1, -1, -1, -1).repeat(NQ, 1, 1, 1), r4(vs)], dim=1).contiguous()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for rep in range(2):
+        e0.record()
+        for j in range(NQ):
+            pool.sk_session_query(sid, qfull[j], kfull[j], vfull[j], want_lse=False)
+        e1.record()
+        torch.cuda.synchronize()
+    indep_ms = e0.elapsed_time(e1)
+    flops = 4.0 * shape.head_dim * shape.n_q_heads * (P + NQ * Sfx) * n_end
+    pool.close()
+    return {"cached_tokens": n, "append_ms": float(np.mean(app)), "question_batch_ms": float(np.mean(bat)),
+            "question_batch_tflops": flops / (np.mean(bat) * 1e-3) / 1e12,
+            "question_batch_mfma_frac": flops / (np.mean(bat) * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "sixty_four_independent_queries_ms": indep_ms, "speedup_vs_independent": indep_ms / float(np.mean(bat)),
+            "timing": "torch events on the launch stream, host launch overhead included"}
+
+
+def multi_tenant(sk, n_sessions=48, steps=6):
+    """Multi-tenant ragged step: 48 sessions (log-uniform 2K-64K cached tokens, 16-token blocks in a
+    seeded random order); each step appends 128-1024 tokens on 16 sessions and queries 8-64 tokens
+    (own K/V) on the other 32; the appended tokens are truncated away again after every step."""
+    shape = synth.CFG4
+    gen = synth.generator(4)
+    lengths = synth.loguniform_lengths(gen, n_sessions)
+    n_blocks = int(1.25 * sum((x + 15) // 16 for x in lengths)) + 16 * 80
+    pool = sk.Pool(shape.dtype, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, 16, n_blocks, max_sessions=n_sessions,
+                   max_batch_tokens=20480)
+    pool.sk_pool_set_alloc_order(synth.permutation(gen, n_blocks))
+    sids = [pool.sk_session_create() for _ in range(n_sessions)]
+    k = synth.draw(gen, (1024, 8, 128), "bf16").cuda()
+    v = synth.draw(gen, (1024, 8, 128), "bf16").cuda()
+    done = [0] * n_sessions
+    while any(d < x for d, x in zip(done, lengths)):     # round-robin growth: interleaved tables
+        for i in range(n_sessions):
+            Lp = min(1024, lengths[i] - done[i])
+            if Lp > 0:
+                pool.sk_session_append(sids[i], None, k[:Lp], v[:Lp])
+                done[i] += Lp
+    times, toks, kv_bytes, flops = [], [], [], []
+    for s in range(steps + 1):
+        order = [int(x) for x in synth.permutation(gen, n_sessions)]
+        ops = [sk.SK_OP_APPEND] * 16 + [sk.SK_OP_QUERY_B] * 32
+        counts = [synth.randint(gen, 128, 1024) for _ in range(16)] + [synth.randint(gen, 8, 64) for _ in range(32)]
+        cu = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+        T = int(cu[-1])
+        q, kk, vv = [t.cuda() for t in synth.draw_qkv(gen, T, shape)]
+        out = torch.empty((T, 32, 128), dtype=torch.float32, device="cuda")
+        lse = torch.empty((T, 32), dtype=torch.float32, device="cuda")
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        pool.sk_batch_step([sids[i] for i in order], ops, cu, q, kk, vv, out=out, lse=lse)
+        e1.record()
+        torch.cuda.synchronize()
+        if s > 0:
+            times.append(e0.elapsed_time(e1)); toks.append(T)
+            flops.append(sum(4.0 * 128 * 32 * c * (lengths[i] + (c + 1) / 2.0) for c, i in zip(counts, order)))
+            kv_bytes.append(sum(lengths[i] * 4096 for i in order[16:]))
+        for j in range(16):
+            pool.sk_session_truncate(sids[order[j]], lengths[order[j]])
+    pool.close()
+    ms = float(np.mean(times))
+    return {"sessions": n_sessions, "cached_tokens_total": int(sum(lengths)), "step_ms": ms,
+            "new_tokens_per_step": float(np.mean(toks)), "tokens_per_s": float(np.mean(toks)) / (ms * 1e-3),
+            "tflops": float(np.mean(flops)) / (ms * 1e-3) / 1e12, "query_kv_GB_per_step": float(np.mean(kv_bytes)) / 1e9,
+            "timing": "torch events on the launch stream, host planning and upload included"}
 
 
 if __name__ == "__main__":
