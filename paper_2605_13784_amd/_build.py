@@ -30,16 +30,29 @@ def build(force: bool = True, verbose: bool = False) -> str:
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [hipcc] + HIPCC_FLAGS + ["-o", tmp] + [os.path.join(CSRC, s) for s in SOURCES]
+    cmd = [hipcc] + HIPCC_FLAGS + ["-Rpass-analysis=kernel-resource-usage", "-o", tmp] + [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:
         print(" ".join(cmd))
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + r.stdout + r.stderr)
-    if verbose and r.stderr:
-        print(r.stderr)
+    check_no_spills(r.stderr)
     os.replace(tmp, LIB)
     return LIB
+
+
+def check_no_spills(remarks: str) -> None:
+    """The MFMA attention kernel counts its own outstanding vector-memory operations
+    (s_waitcnt vmcnt(N) against the direct-to-LDS loads in flight).  Register spills would add
+    scratch loads and stores to that count, so a build in which that kernel spills is refused."""
+    name = None
+    for line in remarks.splitlines():
+        if "Function Name:" in line:
+            name = line.split("Function Name:")[1].split()[0]
+        elif "VGPRs Spill:" in line and name and "sk_attn_bf16" in name:
+            n = int(line.split("VGPRs Spill:")[1].split()[0])
+            if n != 0:
+                raise RuntimeError("kernel %s spills %d VGPRs; its hand-placed vmcnt waits assume none" % (name, n))
 
 
 if __name__ == "__main__":

@@ -152,6 +152,7 @@ __device__ __forceinline__ const unsigned char* sk_group_base(const sk_seg& g, i
 #endif
 #define SK_RESCALE_SLACK 8.0f
 
+template <int N> struct sk_int { static constexpr int value = N; };
 typedef __attribute__((address_space(3))) void* sk_lds_ptr;
 typedef const __attribute__((address_space(1))) void* sk_glb_ptr;
 
@@ -170,9 +171,9 @@ __device__ __forceinline__ void sk_lds_barrier()
 // One direct-to-LDS load of 16 bytes per lane: lane i's data lands at lds_addr + 16 i.
 // Written as inline assembly so that the compiler's automatic wait insertion does not drain the
 // tiles in flight before every LDS read; the waits are placed by hand (SK_WAIT_VMCNT).
-__device__ __forceinline__ void sk_dma16(const void* src, unsigned lds_addr)
-{
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(src) : "memory", "m0");
+__device__ __forceinline__ void sk_dma16(const void* base, unsigned lane_off, unsigned lds_addr)
+{   // address = base (scalar registers) + lane_off (one VGPR, unsigned)
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(lane_off), "s"(base) : "memory", "m0");
 }
 
 // Pool blocks holding the two 16-key groups of the tile that starts at key t0 (scalar loads).
@@ -191,9 +192,15 @@ __device__ __forceinline__ sk_tile_blocks sk_lookup_tile(const sk_seg& g, int t0
     return b;
 }
 
-// Issues the four direct-to-LDS loads with which this wave contributes to one tile.
+// Issues the four direct-to-LDS loads with which this wave contributes to one tile.  The part of
+// every source address that depends on the lane is the same for all tiles of a segment (koff,
+// voff); the rest is uniform and stays in scalar registers.
+//   K   : this wave fills LDS rows 16 j + 4 wave .. + 3 of group j; lane -> (row rr, chunk position),
+//         source chunk (position ^ rr):        koff = rr * 256 + ((lane & 15) ^ rr) * 16
+//   V^T : this wave fills dims 32 wave .. + 31 of group j; lane -> (dim dd, half position),
+//         source half (position ^ bit 3 of dd): voff = dd * 2B + (half ^ ((dd >> 3) & 1)) * 16
 __device__ __forceinline__ void sk_issue_tile(const sk_seg& g, int t0, int last_group, const sk_tile_blocks& tb,
-                                              unsigned stage, int wave, int lane)
+                                              unsigned stage, int wave, unsigned koff, unsigned voff)
 {
 #pragma unroll
     for (int j = 0; j < 2; ++j) {            // j = 16-key group of the tile
@@ -201,20 +208,8 @@ __device__ __forceinline__ void sk_issue_tile(const sk_seg& g, int t0, int last_
         tg = tg < last_group ? tg : last_group;
         const unsigned char* bb = g.base + (int64_t)tb.blk[j] * g.blk_stride;
         const int slot0 = tg & (g.B - 1);
-        // K: this wave fills LDS rows 16 j + 4 wave .. + 3; lane -> (row, chunk position)
-        {
-            const int rr = wave * 4 + (lane >> 4);          // row inside the group
-            const int c = (lane & 15) ^ rr;                 // source chunk for this position
-            const unsigned char* src = bb + (size_t)(slot0 + rr) * 256 + c * 16;
-            sk_dma16(src, stage + (j * 4 + wave) * 1024);
-        }
-        // V^T: this wave fills dims 32 wave .. + 31 of group j; lane -> (dim, half position)
-        {
-            const int dd = wave * 32 + (lane >> 1);
-            const int h = (lane & 1) ^ ((dd >> 3) & 1);
-            const unsigned char* src = bb + g.v_off + (size_t)dd * (2 * g.B) + (slot0 + h * 8) * 2;
-            sk_dma16(src, stage + 8192 + (j * 4 + wave) * 1024);
-        }
+        sk_dma16(bb + (size_t)slot0 * 256, koff, stage + (j * 4 + wave) * 1024);
+        sk_dma16(bb + g.v_off + slot0 * 2, voff, stage + 8192 + (j * 4 + wave) * 1024);
     }
 }
 
@@ -270,7 +265,8 @@ __global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk
                           ((size_t)(w.q_tok0 + (row_valid ? tok_local : 0)) * P.g.Hq + hq) * 256);
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            uint4 x = row_valid ? qp[ks * 2 + kg] : z;
+            uint4 x = qp[ks * 2 + kg];                 // rows past the tile re-read row 0, then zeroed
+            if (!row_valid) x = z;
             qreg[ks] = __builtin_bit_cast(bf16x8, x);
         }
     }
@@ -285,6 +281,19 @@ __global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk
     // key tau(rho): swap bits 2 and 3 of the S^T row index
     const int tau = (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1);
 
+    // lane-dependent LDS addresses of the MFMA operands inside a tile (the XOR swizzles make them
+    // irregular in ks, so they are kept in registers; tile and ring-half offsets are immediates)
+    const unsigned char* kptr[8];
+    const unsigned char* vptr[4];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) kptr[ks] = lds + ph * TPW * SK_TILE_BYTES + tau * 256 + (((ks * 2 + kg) ^ (tau & 15)) << 4);
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+        const int dd = mt * 32 + r;
+        vptr[mt] = lds + ph * TPW * SK_TILE_BYTES + 8192 + dd * 32 + ((kg ^ ((dd >> 3) & 1)) << 4);
+    }
+    static_assert(NSS == 2, "the iteration body is unrolled over the two ring halves");
+
 #pragma unroll 1
     for (int s = 0; s < 3; ++s) {
         sk_seg g = sk_make_seg(P, w, s);
@@ -297,63 +306,60 @@ __global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk
         const int lim_wave_max = p_wave_max < seg_last_pos ? p_wave_max : seg_last_pos;
         const int lim_row = p_row < seg_last_pos ? p_row : seg_last_pos;
 
+        // lane-dependent parts of the DMA source addresses for this segment
+        const unsigned koff = (unsigned)((wave * 4 + (lane >> 4)) * 256 + (((lane & 15) ^ (wave * 4 + (lane >> 4))) << 4));
+        const int vdd = wave * 32 + (lane >> 1);
+        const unsigned voff = (unsigned)(vdd * (2 * g.B) + ((((lane & 1) ^ ((vdd >> 3) & 1))) << 4));
+
         sk_lds_barrier();                      // ring free (previous segment fully consumed)
-        // prologue: iterations 0 .. NSS-2
+        // prologue: iteration 0
+        if (niter > 0) {
 #pragma unroll
-        for (int pi = 0; pi < NSS - 1; ++pi) {
-            if (pi < niter) {
-#pragma unroll
-                for (int p = 0; p < TPI; ++p) {
-                    const int t0 = g.begin + (pi * TPI + p) * SK_TILE;
-                    const sk_tile_blocks tb = sk_lookup_tile(g, t0, last_group);
-                    SK_EXP_LOADS sk_issue_tile(g, t0, last_group, tb, lds_base + ((pi % NSS) * TPI + p) * SK_TILE_BYTES, wave, lane);
-                }
+            for (int p = 0; p < TPI; ++p) {
+                const int t0 = g.begin + p * SK_TILE;
+                const sk_tile_blocks tb = sk_lookup_tile(g, t0, last_group);
+                SK_EXP_LOADS sk_issue_tile(g, t0, last_group, tb, lds_base + p * SK_TILE_BYTES, wave, koff, voff);
             }
         }
         // block ids of the next refill are looked up one iteration ahead of their use
         sk_tile_blocks nb[TPI];
 #pragma unroll
         for (int p = 0; p < TPI; ++p)
-            nb[p] = sk_lookup_tile(g, g.begin + ((NSS - 1) * TPI + p) * SK_TILE, last_group);
+            nb[p] = sk_lookup_tile(g, g.begin + (TPI + p) * SK_TILE, last_group);
         // The query operand must have arrived before the loop (a wait for it placed by the
         // compiler inside the loop would drain the ring on every iteration).
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) asm volatile("" : : "v"(qreg[ks]));
-        for (int it = 0; it < niter; ++it) {
-            // wait for this wave's loads of iteration `it`: at most min(NSS-2, niter-1-it)
-            // later iterations may stay outstanding
-            const int rem = niter - 1 - it;
-            if (NSS >= 4 && rem >= 2) SK_WAIT_VMCNT(2 * LP);
-            else if (NSS >= 3 && rem >= 1) SK_WAIT_VMCNT(1 * LP);
-            else SK_WAIT_VMCNT(0);
+
+        // One iteration (64 keys).  STAGE is the ring half it reads (a compile-time constant, so LDS
+        // offsets fold into the instructions' immediate fields); the other half is being refilled.
+        auto iteration = [&](const int it, auto stage_const) {
+            constexpr int STAGE = decltype(stage_const)::value;
+            SK_WAIT_VMCNT(0);                  // this wave's loads of iteration `it` have landed
             sk_lds_barrier();
-            // refill the stage consumed in iteration it-1 with iteration it+NSS-1 (its block
-            // ids were looked up during the previous iteration), then look up the next ones
-            {
-                const int ni = it + NSS - 1;
-                if (ni < niter) {
+            // refill the half consumed in iteration it-1 with iteration it+1 (its block ids were
+            // looked up during the previous iteration), then look up the next ones
+            if (it + 1 < niter) {
+#pragma unroll
+                for (int p = 0; p < TPI; ++p)
+                    SK_EXP_LOADS sk_issue_tile(g, g.begin + ((it + 1) * TPI + p) * SK_TILE, last_group, nb[p],
+                                               lds_base + ((1 - STAGE) * TPI + p) * SK_TILE_BYTES, wave, koff, voff);
+                if (it + 2 < niter) {
 #pragma unroll
                     for (int p = 0; p < TPI; ++p)
-                        SK_EXP_LOADS sk_issue_tile(g, g.begin + (ni * TPI + p) * SK_TILE, last_group, nb[p],
-                                                   lds_base + ((ni % NSS) * TPI + p) * SK_TILE_BYTES, wave, lane);
-                    if (ni + 1 < niter) {
-#pragma unroll
-                        for (int p = 0; p < TPI; ++p)
-                            nb[p] = sk_lookup_tile(g, g.begin + ((ni + 1) * TPI + p) * SK_TILE, last_group);
-                    }
+                        nb[p] = sk_lookup_tile(g, g.begin + ((it + 2) * TPI + p) * SK_TILE, last_group);
                 }
             }
-
             // this wave's TPW consecutive tiles of the iteration
             const int tile0 = it * TPI + ph * TPW;
-            const unsigned char* buf = lds + ((it % NSS) * TPI + ph * TPW) * SK_TILE_BYTES;
             const int pos_first = g.begin + tile0 * SK_TILE + g.pos_shift;
             bool active = wave_has_rows && tile0 < ntiles && pos_first <= lim_wave_max;
 #ifdef SK_EXPERIMENT
             if (P.pad & 1) active = false;      // stream only: no arithmetic
 #endif
-            if (!active) continue;
+            if (!active) return;
             const bool need_mask = pos_first + TPW * SK_TILE - 1 > lim_wave_min;
+            constexpr int SOFF = STAGE * TPI * SK_TILE_BYTES;       // byte offset of this ring half
 
             // S^T = K Q^T, TPW independent accumulator chains
             f32x16 sacc[TPW];
@@ -362,13 +368,12 @@ __global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk
 #pragma unroll
                 for (int v = 0; v < 16; ++v) sacc[t][v] = 0.f;
             {
-                const int sw = tau & 15;
                 uint4 ka[TPW][8];
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
                     for (int t = 0; t < TPW; ++t)
-                        ka[t][ks] = *(const uint4*)(buf + t * SK_TILE_BYTES + tau * 256 + (((ks * 2 + kg) ^ sw) << 4));
+                        ka[t][ks] = *(const uint4*)(kptr[ks] + SOFF + t * SK_TILE_BYTES);
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
@@ -385,11 +390,10 @@ __global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk
 #pragma unroll
                 for (int q = 0; q < 2; ++q)
 #pragma unroll
-                    for (int mt = 0; mt < 4; ++mt) {
-                        const int dd = mt * 32 + r;
-                        va[t][q][mt] = *(const uint4*)(buf + t * SK_TILE_BYTES + 8192 + q * 4096 + dd * 32 + ((kg ^ ((dd >> 3) & 1)) << 4));
-                    }
-            // scale to log2 units, mask (only tiles that cross a limit), row maximum
+                    for (int mt = 0; mt < 4; ++mt)
+                        va[t][q][mt] = *(const uint4*)(vptr[mt] + SOFF + t * SK_TILE_BYTES + q * 4096);
+            // mask (only tiles that cross a limit) and row maximum, on the raw scores; the softmax
+            // scale is applied inside the exponent below (one FMA per score)
             float mt_ = SK_NEG_INF;
             if (need_mask) {
 #pragma unroll
@@ -397,7 +401,7 @@ __global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int pos = pos_first + t * SK_TILE + 16 * (v >> 3) + 8 * kg + (v & 7);
-                        const float x = (pos <= lim_row) ? sacc[t][v] * c_scale : SK_NEG_INF;
+                        const float x = (pos <= lim_row) ? sacc[t][v] : SK_NEG_INF;
                         sacc[t][v] = x;
                         mt_ = fmaxf(mt_, x);
                     }
@@ -405,13 +409,9 @@ __global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk
 #pragma unroll
                 for (int t = 0; t < TPW; ++t)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const float x = sacc[t][v] * c_scale;
-                        sacc[t][v] = x;
-                        mt_ = fmaxf(mt_, x);
-                    }
+                    for (int v = 0; v < 16; ++v) mt_ = fmaxf(mt_, sacc[t][v]);
             }
-            mt_ = fmaxf(mt_, __shfl_xor(mt_, 32, 64));
+            mt_ = fmaxf(mt_, __shfl_xor(mt_, 32, 64)) * c_scale;      // log2 units (c_scale > 0)
             const bool raise = mt_ > m_ref + SK_RESCALE_SLACK;
             if (__any(raise)) {
                 const float alpha = raise ? sk_exp2(m_ref - mt_) : 1.0f;
@@ -422,14 +422,14 @@ __global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk
                     for (int v = 0; v < 16; ++v) oacc[mt][v] *= alpha;
                 m_ref = raise ? mt_ : m_ref;
             }
-            const float m_use = (m_ref == SK_NEG_INF) ? 0.f : m_ref;
-            // P = exp2(x - m), row sums, O^T += V^T P^T
+            const float neg_m = (m_ref == SK_NEG_INF) ? 0.f : -m_ref;
+            // P = exp2(s * scale - m), row sums, O^T += V^T P^T
             bf16x8 pb[TPW][2];
 #pragma unroll
             for (int t = 0; t < TPW; ++t)
 #pragma unroll
                 for (int v = 0; v < 8; ++v) {
-                    const float p0 = sk_exp2(sacc[t][v] - m_use), p1 = sk_exp2(sacc[t][8 + v] - m_use);
+                    const float p0 = sk_exp2(fmaf(sacc[t][v], c_scale, neg_m)), p1 = sk_exp2(fmaf(sacc[t][8 + v], c_scale, neg_m));
                     l_run += p0 + p1;
                     pb[t][0][v] = (__bf16)p0;
                     pb[t][1][v] = (__bf16)p1;
@@ -441,6 +441,10 @@ __global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk
 #pragma unroll
                     for (int mt = 0; mt < 4; ++mt)
                         oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[t][q][mt]), pb[t][q], oacc[mt], 0, 0, 0);
+        };
+        for (int it = 0; it < niter; it += 2) {
+            iteration(it, sk_int<0>{});
+            if (it + 1 < niter) iteration(it + 1, sk_int<1>{});
         }
     }
 

@@ -61,7 +61,7 @@ def test_bf16_gqa_ragged_appends_and_queries(block_tokens):
 
 def test_bf16_first_tokens_short_context():
     """Short contexts (n < 16), where the bf16 rounding of the softmax weights weighs most, and
-    the very first token of an empty session (output = its own value)."""
+    the very first token of an empty session (output = its own value, to fp32 rounding)."""
     shape = synth.CFG2
     gen = synth.generator(2, stream=2)
     pr = Pair(shape, n_blocks=16, kv_fill=0xFF)
@@ -71,7 +71,8 @@ def test_bf16_first_tokens_short_context():
     G = shape.group
     torch.cuda.synchronize()
     expect = v.float().repeat_interleave(G, dim=1)
-    assert torch.equal(out.cpu(), expect)
+    # one key: the weight is exp2(fma(s, c, -round(s*c))), which is 1 up to one rounding of s*c
+    assert torch.allclose(out.cpu(), expect, rtol=1e-6, atol=0)
     for L in [1, 2, 3, 5]:
         q, k, v = synth.draw_qkv(gen, L, shape)
         pr.append(sid, q, k, v, name="short append L=%d" % L)
