@@ -374,11 +374,13 @@ __global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk
 #pragma unroll
                     for (int t = 0; t < TPW; ++t)
                         ka[t][ks] = *(const uint4*)(kptr[ks] + SOFF + t * SK_TILE_BYTES);
+                __builtin_amdgcn_s_setprio(2);     // the wave feeding the matrix pipe goes first
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
                     for (int t = 0; t < TPW; ++t)
                         sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[t][ks]), qreg[ks], sacc[t], 0, 0, 0);
+                __builtin_amdgcn_s_setprio(0);
                 // all LDS reads first, then the MFMAs back to back (two independent chains)
                 __builtin_amdgcn_sched_group_barrier(0x100, 8 * TPW, 0);
                 __builtin_amdgcn_sched_group_barrier(0x008, 8 * TPW, 0);
