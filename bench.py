@@ -33,7 +33,12 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per dispatch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (fetch + write),
 # scaled by a 1 GiB device copy; see profiles/bench_cfg2_attention_kernels.md for the runs.
 # Keyed by (workload, block_tokens, cache state); other configurations report null.
-MEASURED_HBM_TRAFFIC = {}
+MEASURED_HBM_TRAFFIC = {
+    ("cfg2_llama3_8b_layer_32k", 16, "cold"): {
+        "query": {"fetch_bytes": 134.95e6, "write_bytes": 17.04e6, "total_bytes": 151.99e6},
+        "append": {"fetch_bytes": 136.77e6, "write_bytes": 34.08e6, "total_bytes": 170.85e6},
+    },
+}
 
 WORKLOADS = {
     # name: (shape, cached tokens at query time, append chunk, query tokens)
