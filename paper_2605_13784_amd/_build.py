@@ -49,10 +49,11 @@ def check_no_spills(remarks: str) -> None:
     for line in remarks.splitlines():
         if "Function Name:" in line:
             name = line.split("Function Name:")[1].split()[0]
-        elif "VGPRs Spill:" in line and name and "sk_attn_bf16" in name:
-            n = int(line.split("VGPRs Spill:")[1].split()[0])
-            if n != 0:
-                raise RuntimeError("kernel %s spills %d VGPRs; its hand-placed vmcnt waits assume none" % (name, n))
+        elif name and "sk_attn_bf16" in name:
+            for key in ("VGPRs Spill:", "ScratchSize [bytes/lane]:"):
+                if key in line and int(line.split(key)[1].split()[0]) != 0:
+                    raise RuntimeError("kernel %s uses scratch memory (%s); its hand-placed vmcnt waits assume none"
+                                       % (name, line.split("remark:")[-1].strip()))
 
 
 if __name__ == "__main__":

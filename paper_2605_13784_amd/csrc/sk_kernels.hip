@@ -144,16 +144,15 @@ __device__ __forceinline__ const unsigned char* sk_group_base(const sk_seg& g, i
 // ---------------------------------------------------------------------------------------------
 #define SK_TILE 32                 // keys per tile
 #define SK_TILE_BYTES 16384        // K 8 KiB | V^T 8 KiB
-#ifndef SK_NST
-#define SK_NST 4                   // ring depth in tiles
-#endif
-#ifndef SK_WGS_PER_CU
-#define SK_WGS_PER_CU 2            // workgroups per CU the register budget is sized for
-#endif
 #define SK_RESCALE_SLACK 8.0f
 
 template <int N> struct sk_int { static constexpr int value = N; };
 typedef __attribute__((address_space(3))) void* sk_lds_ptr;
+// LDS operand addresses are kept in the LDS address space explicitly: through a generic pointer
+// the compiler may fall back to flat loads, which also count as vector memory operations.
+typedef const __attribute__((address_space(3))) unsigned char* sk_lds_cptr;
+typedef __attribute__((ext_vector_type(4))) unsigned sk_u32x4;       // one 16-byte MFMA operand
+typedef const __attribute__((address_space(3))) sk_u32x4* sk_lds_u4ptr;
 typedef const __attribute__((address_space(1))) void* sk_glb_ptr;
 
 // s_waitcnt vmcnt(n) only (gfx9 encoding: vmcnt = simm16[3:0] | simm16[15:14] << 4)
@@ -192,15 +191,18 @@ __device__ __forceinline__ sk_tile_blocks sk_lookup_tile(const sk_seg& g, int t0
     return b;
 }
 
-// Issues the four direct-to-LDS loads with which this wave contributes to one tile.  The part of
-// every source address that depends on the lane is the same for all tiles of a segment (koff,
-// voff); the rest is uniform and stays in scalar registers.
-//   K   : this wave fills LDS rows 16 j + 4 wave .. + 3 of group j; lane -> (row rr, chunk position),
+// Issues the four direct-to-LDS loads with which one of four waves (`sub` = 0..3) contributes to
+// one tile: a K and a V^T load for each of the tile's two 16-key groups.  The part of every source
+// address that depends on the lane is the same for all tiles of a segment (koff, voff); the rest
+// is uniform and stays in scalar registers.
+//   K   : the wave fills LDS rows 16 j + 4 sub .. + 3 of group j; lane -> (row rr, chunk position),
 //         source chunk (position ^ rr):        koff = rr * 256 + ((lane & 15) ^ rr) * 16
-//   V^T : this wave fills dims 32 wave .. + 31 of group j; lane -> (dim dd, half position),
+//   V^T : the wave fills dims 32 sub .. + 31 of group j; lane -> (dim dd, half position),
 //         source half (position ^ bit 3 of dd): voff = dd * 2B + (half ^ ((dd >> 3) & 1)) * 16
+// In LDS the sixteen 1 KiB units of a tile (K units 0-7, V^T units 8-15) lie `us` bytes apart, with
+// the same unit of the other tiles of the ring in between; `tile_addr` is the address of unit 0.
 __device__ __forceinline__ void sk_issue_tile(const sk_seg& g, int t0, int last_group, const sk_tile_blocks& tb,
-                                              unsigned stage, int wave, unsigned koff, unsigned voff)
+                                              unsigned tile_addr, unsigned us, int sub, unsigned koff, unsigned voff)
 {
 #pragma unroll
     for (int j = 0; j < 2; ++j) {            // j = 16-key group of the tile
@@ -208,27 +210,35 @@ __device__ __forceinline__ void sk_issue_tile(const sk_seg& g, int t0, int last_
         tg = tg < last_group ? tg : last_group;
         const unsigned char* bb = g.base + (int64_t)tb.blk[j] * g.blk_stride;
         const int slot0 = tg & (g.B - 1);
-        sk_dma16(bb + (size_t)slot0 * 256, koff, stage + (j * 4 + wave) * 1024);
-        sk_dma16(bb + g.v_off + slot0 * 2, voff, stage + 8192 + (j * 4 + wave) * 1024);
+        sk_dma16(bb + (size_t)slot0 * 256, koff, tile_addr + (j * 4 + sub) * us);
+        sk_dma16(bb + g.v_off + slot0 * 2, voff, tile_addr + (8 + j * 4 + sub) * us);
     }
 }
 
 #ifdef SK_EXPERIMENT              // development builds: P.pad bit 0 = no arithmetic, bit 1 = no loads
 #define SK_EXP_LOADS if (!(P.pad & 2))
+// bit 6: waves 0 and 4 of workgroup 0 record the cycle counter at slot boundaries
+#define SK_STAMP() do { if ((P.pad & 64) && blockIdx.x == 0 && lane == 0 && (wave & 3) == 0 && stamp_n < 1024) \
+        ((long long*)P.work)[(wave >> 2) * 1024 + stamp_n++] = clock64(); } while (0)
 #else
 #define SK_EXP_LOADS
+#define SK_STAMP() do { } while (0)
 #endif
 
-template <int NPH>
-__global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk_launch P)
+template <int NRG, int NPH, int NSS>
+__global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_attn_bf16_d128(const sk_launch P)
 {
-    constexpr int NRG = 4 / NPH;
+    constexpr int NW = NRG * NPH;            // waves: 4 or 8
     constexpr int TPI = 2;                   // tiles per iteration (64 keys)
     constexpr int TPW = TPI / NPH;           // tiles per wave per iteration
-    constexpr int NSS = SK_NST / TPI;        // ring depth in iterations
-    constexpr int LP = 4 * TPI;              // loads per wave per iteration
-    static_assert(SK_NST % TPI == 0 && NSS >= 2, "ring depth");
-    __shared__ __attribute__((aligned(16))) unsigned char lds[SK_NST * SK_TILE_BYTES];
+    static_assert(NW == 4 || (NW == 8 && NPH == 1 && NSS == 4), "four waves, or eight in two alternating groups");
+    static_assert(NSS == 2 || NSS == 4, "ring depth in iterations: 64 KiB (two workgroups per CU) or 128 KiB (one)");
+    // The ring holds NSS iterations of TPI tiles.  Its 1 KiB units are interleaved: unit u of tile t
+    // of ring slot s sits at (u * TPI * NSS + t * NSS + s) KiB, so that from a lane's per-unit base
+    // address every tile of the ring is within reach of the 16-bit offset field of an LDS read.
+    constexpr unsigned US = TPI * NSS * 1024;                 // bytes from unit u to unit u + 1
+#define SK_SLOT_OFF(s, t) (((t) * NSS + (s)) * 1024)          // tile t of ring slot s, relative to unit bases
+    __shared__ __attribute__((aligned(16))) unsigned char lds[NSS * TPI * SK_TILE_BYTES];
 
     sk_work w;
     if (!sk_decode_work(P, blockIdx.x, w)) return;
@@ -237,9 +247,22 @@ __global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk
     if (P.pad & 4) return;                     // launch overhead only
 #endif
     const unsigned lds_base = (unsigned)(uintptr_t)(sk_lds_ptr)lds;   // LDS byte address of the ring
+#ifdef SK_EXPERIMENT
+    int stamp_n = 0;
+#endif
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // in a scalar register
     const int rg = wave % NRG, ph = wave / NRG;
+    // Eight waves work as two groups of four that alternate between the matrix pipe and the vector
+    // ALU (see the segment loop).  Waves i and i + 4 of a workgroup share a SIMD, so a SIMD holds
+    // one wave of each group.  `sub` is the wave's index among the four that load a tile.
+#ifdef SK_EXPERIMENT
+    const int grp = NW == 8 ? ((P.pad & 32) ? (wave & 1) : (wave >> 2)) : 0;
+    const int sub = NW == 8 ? ((P.pad & 32) ? (wave >> 1) : (wave & 3)) : wave;
+#else
+    const int grp = NW == 8 ? (wave >> 2) : 0;
+    const int sub = wave & 3;
+#endif
     const int r = lane & 31, kg = lane >> 5;
     const int log2G = P.g.log2G, G = P.g.G;
     const int row_in_tile = rg * 32 + r;
@@ -282,17 +305,17 @@ __global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk
     const int tau = (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1);
 
     // lane-dependent LDS addresses of the MFMA operands inside a tile (the XOR swizzles make them
-    // irregular in ks, so they are kept in registers; tile and ring-half offsets are immediates)
-    const unsigned char* kptr[8];
-    const unsigned char* vptr[4];
+    // irregular in ks, so they are kept in registers; tile and ring-slot offsets are immediates)
+    sk_lds_cptr kptr[8];
+    sk_lds_cptr vptr[4];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) kptr[ks] = lds + ph * TPW * SK_TILE_BYTES + tau * 256 + (((ks * 2 + kg) ^ (tau & 15)) << 4);
+    for (int ks = 0; ks < 8; ++ks)       // K row tau is row tau % 4 of unit tau / 4
+        kptr[ks] = (sk_lds_cptr)lds + SK_SLOT_OFF(0, ph * TPW) + (tau >> 2) * US + (tau & 3) * 256 + (((ks * 2 + kg) ^ (tau & 15)) << 4);
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
         const int dd = mt * 32 + r;
-        vptr[mt] = lds + ph * TPW * SK_TILE_BYTES + 8192 + dd * 32 + ((kg ^ ((dd >> 3) & 1)) << 4);
+        vptr[mt] = (sk_lds_cptr)lds + SK_SLOT_OFF(0, ph * TPW) + (8 + mt) * US + r * 32 + ((kg ^ ((dd >> 3) & 1)) << 4);   // 16-key group q: + 4 q units
     }
-    static_assert(NSS == 2, "the iteration body is unrolled over the two ring halves");
 
 #pragma unroll 1
     for (int s = 0; s < 3; ++s) {
@@ -307,95 +330,65 @@ __global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk
         const int lim_row = p_row < seg_last_pos ? p_row : seg_last_pos;
 
         // lane-dependent parts of the DMA source addresses for this segment
-        const unsigned koff = (unsigned)((wave * 4 + (lane >> 4)) * 256 + (((lane & 15) ^ (wave * 4 + (lane >> 4))) << 4));
-        const int vdd = wave * 32 + (lane >> 1);
+        const unsigned koff = (unsigned)((sub * 4 + (lane >> 4)) * 256 + (((lane & 15) ^ (sub * 4 + (lane >> 4))) << 4));
+        const int vdd = sub * 32 + (lane >> 1);
         const unsigned voff = (unsigned)(vdd * (2 * g.B) + ((((lane & 1) ^ ((vdd >> 3) & 1))) << 4));
 
-        sk_lds_barrier();                      // ring free (previous segment fully consumed)
-        // prologue: iteration 0
-        if (niter > 0) {
-#pragma unroll
-            for (int p = 0; p < TPI; ++p) {
-                const int t0 = g.begin + p * SK_TILE;
-                const sk_tile_blocks tb = sk_lookup_tile(g, t0, last_group);
-                SK_EXP_LOADS sk_issue_tile(g, t0, last_group, tb, lds_base + p * SK_TILE_BYTES, wave, koff, voff);
-            }
-        }
-        // block ids of the next refill are looked up one iteration ahead of their use
-        sk_tile_blocks nb[TPI];
-#pragma unroll
-        for (int p = 0; p < TPI; ++p)
-            nb[p] = sk_lookup_tile(g, g.begin + (TPI + p) * SK_TILE, last_group);
-        // The query operand must have arrived before the loop (a wait for it placed by the
-        // compiler inside the loop would drain the ring on every iteration).
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) asm volatile("" : : "v"(qreg[ks]));
+        // ---- the three steps of one iteration (64 keys) for this wave; the ring slot is a
+        // compile-time constant so that it folds into the offset field of the LDS instructions ----
+        f32x16 sacc[TPW];          // S^T of the iteration in flight
+        sk_u32x4 va[TPW][2][4];       // its V^T operands (four waves)
+        sk_u32x4 va0[4];              // V^T operands of the first 16 keys (eight waves)
+        bf16x8 pb[TPW][2];         // its P^T operands
 
-        // One iteration (64 keys).  STAGE is the ring half it reads (a compile-time constant, so LDS
-        // offsets fold into the instructions' immediate fields); the other half is being refilled.
-        auto iteration = [&](const int it, auto stage_const) {
-            constexpr int STAGE = decltype(stage_const)::value;
-            SK_WAIT_VMCNT(0);                  // this wave's loads of iteration `it` have landed
-            sk_lds_barrier();
-            // refill the half consumed in iteration it-1 with iteration it+1 (its block ids were
-            // looked up during the previous iteration), then look up the next ones
-            if (it + 1 < niter) {
-#pragma unroll
-                for (int p = 0; p < TPI; ++p)
-                    SK_EXP_LOADS sk_issue_tile(g, g.begin + ((it + 1) * TPI + p) * SK_TILE, last_group, nb[p],
-                                               lds_base + ((1 - STAGE) * TPI + p) * SK_TILE_BYTES, wave, koff, voff);
-                if (it + 2 < niter) {
-#pragma unroll
-                    for (int p = 0; p < TPI; ++p)
-                        nb[p] = sk_lookup_tile(g, g.begin + ((it + 2) * TPI + p) * SK_TILE, last_group);
-                }
-            }
-            // this wave's TPW consecutive tiles of the iteration
-            const int tile0 = it * TPI + ph * TPW;
-            const int pos_first = g.begin + tile0 * SK_TILE + g.pos_shift;
-            bool active = wave_has_rows && tile0 < ntiles && pos_first <= lim_wave_max;
+        // first key position of the wave's tiles of iteration `it`, and whether it has work there
+        auto first_pos = [&](const int it) __attribute__((always_inline)) { return g.begin + (it * TPI + ph * TPW) * SK_TILE + g.pos_shift; };
+        auto is_active = [&](const int it) __attribute__((always_inline)) {
+            bool a = wave_has_rows && it * TPI + ph * TPW < ntiles && first_pos(it) <= lim_wave_max;
 #ifdef SK_EXPERIMENT
-            if (P.pad & 1) active = false;      // stream only: no arithmetic
+            if (P.pad & 1) a = false;           // stream only: no arithmetic
 #endif
-            if (!active) return;
-            const bool need_mask = pos_first + TPW * SK_TILE - 1 > lim_wave_min;
-            constexpr int SOFF = STAGE * TPI * SK_TILE_BYTES;       // byte offset of this ring half
+            return a;
+        };
 
-            // S^T = K Q^T, TPW independent accumulator chains
-            f32x16 sacc[TPW];
+        // S^T = K Q^T, TPW independent accumulator chains
+        auto step_scores = [&](auto stage_const) __attribute__((always_inline)) {
+            constexpr int STAGE = decltype(stage_const)::value;
 #pragma unroll
             for (int t = 0; t < TPW; ++t)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) sacc[t][v] = 0.f;
-            {
-                uint4 ka[TPW][8];
+            sk_u32x4 ka[TPW][8];
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks)
+            for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
-                    for (int t = 0; t < TPW; ++t)
-                        ka[t][ks] = *(const uint4*)(kptr[ks] + SOFF + t * SK_TILE_BYTES);
-                __builtin_amdgcn_s_setprio(2);     // the wave feeding the matrix pipe goes first
+                for (int t = 0; t < TPW; ++t)
+                    ka[t][ks] = *(sk_lds_u4ptr)(kptr[ks] + SK_SLOT_OFF(STAGE, t));
+            __builtin_amdgcn_s_setprio(2);     // the wave feeding the matrix pipe goes first
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks)
+            for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
-                    for (int t = 0; t < TPW; ++t)
-                        sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[t][ks]), qreg[ks], sacc[t], 0, 0, 0);
-                __builtin_amdgcn_s_setprio(0);
-                // all LDS reads first, then the MFMAs back to back (two independent chains)
-                __builtin_amdgcn_sched_group_barrier(0x100, 8 * TPW, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 8 * TPW, 0);
-            }
-            // V^T operands are requested now, so that their LDS latency hides behind the softmax
-            uint4 va[TPW][2][4];
+                for (int t = 0; t < TPW; ++t)
+                    sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[t][ks]), qreg[ks], sacc[t], 0, 0, 0);
+            __builtin_amdgcn_s_setprio(0);
+            // all LDS reads first, then the MFMAs back to back (two independent chains)
+            __builtin_amdgcn_sched_group_barrier(0x100, 8 * TPW, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 8 * TPW, 0);
+        };
+        auto load_v_tile = [&](const int t, auto stage_const) __attribute__((always_inline)) {
+            constexpr int STAGE = decltype(stage_const)::value;
 #pragma unroll
-            for (int t = 0; t < TPW; ++t)
+            for (int q = 0; q < 2; ++q)
 #pragma unroll
-                for (int q = 0; q < 2; ++q)
-#pragma unroll
-                    for (int mt = 0; mt < 4; ++mt)
-                        va[t][q][mt] = *(const uint4*)(vptr[mt] + SOFF + t * SK_TILE_BYTES + q * 4096);
-            // mask (only tiles that cross a limit) and row maximum, on the raw scores; the softmax
-            // scale is applied inside the exponent below (one FMA per score)
+                for (int mt = 0; mt < 4; ++mt)
+                    va[t][q][mt] = *(sk_lds_u4ptr)(vptr[mt] + SK_SLOT_OFF(STAGE, t) + q * 4 * US);
+        };
+        // mask (only tiles that cross a limit), row maximum, P = exp2(s * scale - m), row sums
+        auto step_softmax = [&](const int it) __attribute__((always_inline)) {
+            const int pos_first = first_pos(it);
+            const bool need_mask = pos_first + TPW * SK_TILE - 1 > lim_wave_min;
+            // the maximum is taken on the raw scores; the softmax scale is applied inside the
+            // exponent below (one FMA per score)
             float mt_ = SK_NEG_INF;
             if (need_mask) {
 #pragma unroll
@@ -425,8 +418,6 @@ __global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk
                 m_ref = raise ? mt_ : m_ref;
             }
             const float neg_m = (m_ref == SK_NEG_INF) ? 0.f : -m_ref;
-            // P = exp2(s * scale - m), row sums, O^T += V^T P^T
-            bf16x8 pb[TPW][2];
 #pragma unroll
             for (int t = 0; t < TPW; ++t)
 #pragma unroll
@@ -436,17 +427,238 @@ __global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk
                     pb[t][0][v] = (__bf16)p0;
                     pb[t][1][v] = (__bf16)p1;
                 }
+        };
+        // O^T += V^T P^T for one tile
+        auto pv_tile = [&](const int t) __attribute__((always_inline)) {
 #pragma unroll
-            for (int t = 0; t < TPW; ++t)
+            for (int q = 0; q < 2; ++q)
 #pragma unroll
-                for (int q = 0; q < 2; ++q)
+                for (int mt = 0; mt < 4; ++mt)
+                    oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[t][q][mt]), pb[t][q], oacc[mt], 0, 0, 0);
+        };
+
+        sk_lds_barrier();                      // ring free (previous segment fully consumed)
+        // The query operand must have arrived before the loop (a wait for it placed by the
+        // compiler inside the loop would drain the ring on every iteration).
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) asm volatile("" : : "v"(qreg[ks]));
+
+        if constexpr (NW == 4) {
+            // ---- four waves: every wave walks S, softmax, PV of an iteration in turn; overlap of
+            // matrix and vector work comes from the other workgroup on the CU ----
+            constexpr int LPW = 4 * TPI;         // direct-to-LDS loads per wave per iteration
+            // prologue: iterations 0 .. NSS-2
+#pragma unroll
+            for (int a = 0; a < NSS - 1; ++a) {
+                if (a < niter) {
+#pragma unroll
+                    for (int p = 0; p < TPI; ++p) {
+                        const int t0 = g.begin + (a * TPI + p) * SK_TILE;
+                        const sk_tile_blocks tb = sk_lookup_tile(g, t0, last_group);
+                        SK_EXP_LOADS sk_issue_tile(g, t0, last_group, tb, lds_base + SK_SLOT_OFF(a, p), US, sub, koff, voff);
+                    }
+                }
+            }
+            // block ids of the next refill are looked up one iteration ahead of their use
+            sk_tile_blocks nb[TPI];
+#pragma unroll
+            for (int p = 0; p < TPI; ++p)
+                nb[p] = sk_lookup_tile(g, g.begin + ((NSS - 1) * TPI + p) * SK_TILE, last_group);
+
+            // STAGE is the ring slot the iteration reads; the slot read by the previous iteration is
+            // refilled with iteration it + NSS - 1.
+            auto iteration = [&](const int it, auto stage_const) __attribute__((always_inline)) {
+                constexpr int STAGE = decltype(stage_const)::value;
+                // this wave's loads of iteration `it` have landed: everything but the loads of the
+                // (at most NSS - 2) later iterations already issued
+                const int later = niter - 1 - it;
+                if (NSS == 2 || later <= 0) SK_WAIT_VMCNT(0);
+                else if (later == 1) SK_WAIT_VMCNT(LPW);
+                else SK_WAIT_VMCNT(2 * LPW);
+                sk_lds_barrier();
+                if (it + NSS - 1 < niter) {
+#pragma unroll
+                    for (int p = 0; p < TPI; ++p)
+                        SK_EXP_LOADS sk_issue_tile(g, g.begin + ((it + NSS - 1) * TPI + p) * SK_TILE, last_group, nb[p],
+                                                   lds_base + SK_SLOT_OFF((STAGE + NSS - 1) % NSS, p), US, sub, koff, voff);
+                    if (it + NSS < niter) {
+#pragma unroll
+                        for (int p = 0; p < TPI; ++p)
+                            nb[p] = sk_lookup_tile(g, g.begin + ((it + NSS) * TPI + p) * SK_TILE, last_group);
+                    }
+                }
+                if (!is_active(it)) return;
+                step_scores(sk_int<STAGE>{});
+#pragma unroll
+                for (int t = 0; t < TPW; ++t) load_v_tile(t, sk_int<STAGE>{});   // requested now: their LDS latency hides behind the softmax
+                step_softmax(it);
+#pragma unroll
+                for (int t = 0; t < TPW; ++t) pv_tile(t);
+            };
+            for (int it = 0; it < niter; it += NSS) {
+                iteration(it, sk_int<0>{});
+                if (it + 1 < niter) iteration(it + 1, sk_int<1>{});
+                if (NSS == 4) {
+                    if (it + 2 < niter) iteration(it + 2, sk_int<2>{});
+                    if (it + 3 < niter) iteration(it + 3, sk_int<3>{});
+                }
+            }
+        } else {
+            // ---- eight waves in two groups of four that take turns.  Every wave alternates between
+            // a matrix slot (P V of iteration j-1, then S of iteration j) and a vector slot (softmax
+            // of iteration j), with a workgroup barrier in front of each; group 1 runs the same
+            // sequence one barrier behind group 0, so that whenever one group is in a matrix slot the
+            // other is in a vector slot.  A SIMD holds one wave of each group: its matrix pipe and
+            // its vector ALU are busy at the same time.
+            //   barrier number    2j              2j+1            2j+2
+            //   group 0           | PV(j-1) S(j)  | softmax(j)    | PV(j) S(j+1)
+            //   group 1           | softmax(j-1)  | PV(j-1) S(j)  | softmax(j)
+            // Iteration i lives in ring slot i % 4 and is read between barriers 2i and 2i+4.  Group
+            // 0 loads the second tile of every iteration, group 1 the first; a wave issues the loads
+            // of iteration j + 2 + grp at the start of its vector slot j (after barrier 2j+1+grp >=
+            // 2(j + grp - 2) + 4, so the ring slot is free) and waits for its loads of iteration i
+            // before its barrier number 2i, after which the whole iteration is in LDS.
+            // The ring slot is a run-time value here (one copy of the loop body): the operand
+            // addresses of the current slot are rebuilt from the per-unit bases once per iteration.
+            // Every wave does every iteration (rows or keys that do not count are masked): the slots
+            // are synchronised, so skipping work would not save time.
+            constexpr int LPW = 4;               // direct-to-LDS loads per wave per iteration (one tile)
+            const int my_tile = 1 - grp;
+            const int ahead = 2 + grp;           // iterations loaded before the loop
+#pragma unroll
+            for (int a = 0; a < 3; ++a) {
+                if (a < ahead && a < niter) {
+                    const int t0 = g.begin + (a * TPI + my_tile) * SK_TILE;
+                    const sk_tile_blocks tb = sk_lookup_tile(g, t0, last_group);
+                    SK_EXP_LOADS sk_issue_tile(g, t0, last_group, tb, lds_base + SK_SLOT_OFF(a, my_tile), US, sub, koff, voff);
+                }
+            }
+            sk_tile_blocks nb = sk_lookup_tile(g, g.begin + (ahead * TPI + my_tile) * SK_TILE, last_group);
+            {   // iteration 0 has landed: all but the loads of the later iterations issued above
+                const int issued = niter < ahead ? niter : ahead;
+                if (issued >= 3) SK_WAIT_VMCNT(2 * LPW); else if (issued == 2) SK_WAIT_VMCNT(LPW); else SK_WAIT_VMCNT(0);
+            }
+            if (grp == 1) sk_lds_barrier();      // group 1 stays one barrier behind
+            // wait for this wave's loads of iteration i; those of iteration i + 1 may still be in flight
+            auto wait_iteration = [&](const int i) __attribute__((always_inline)) {
+                if (i + 1 < niter) SK_WAIT_VMCNT(LPW); else SK_WAIT_VMCNT(0);
+            };
+            auto refill = [&](const int j) __attribute__((always_inline)) {
+                const int i = j + ahead;
+                if (i < niter) {
+                    SK_EXP_LOADS sk_issue_tile(g, g.begin + (i * TPI + my_tile) * SK_TILE, last_group, nb,
+                                               lds_base + SK_SLOT_OFF(i & 3, my_tile), US, sub, koff, voff);
+                    if (i + 1 < niter) nb = sk_lookup_tile(g, g.begin + ((i + 1) * TPI + my_tile) * SK_TILE, last_group);
+                }
+            };
+            // Matrix slot: eight groups of four matrix instructions, P V of the previous iteration
+            // (V^T through vp, the pointers of its ring slot) and S of the current one (K through
+            // kc).  Operands stream from LDS two groups ahead of their use, into the registers that
+            // earlier groups have released (the scheduling barriers keep that order); the first
+            // group's were read in the vector slot.  KIND 0: first slot of a segment, S only;
+            // 2: last slot, P V only.
+            auto matrix_slot = [&](auto kind_const, const int j, const sk_lds_cptr (&kc)[8], const sk_lds_cptr (&vp)[4])
+                                   __attribute__((always_inline)) {
+                constexpr int KIND = decltype(kind_const)::value;
+#ifdef SK_EXPERIMENT
+                if (P.pad & 1) return;              // stream only: no arithmetic
+#endif
+                auto ld_v = [&](sk_u32x4 (&o)[4], const int t, const int q) __attribute__((always_inline)) {
+#pragma unroll
+                    for (int mt = 0; mt < 4; ++mt) o[mt] = *(sk_lds_u4ptr)(vp[mt] + SK_SLOT_OFF(0, t) + q * 4 * US);
+                };
+                auto mm_v = [&](const sk_u32x4 (&o)[4], const int t, const int q) __attribute__((always_inline)) {
 #pragma unroll
                     for (int mt = 0; mt < 4; ++mt)
-                        oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[t][q][mt]), pb[t][q], oacc[mt], 0, 0, 0);
-        };
-        for (int it = 0; it < niter; it += 2) {
-            iteration(it, sk_int<0>{});
-            if (it + 1 < niter) iteration(it + 1, sk_int<1>{});
+                        oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, o[mt]), pb[t][q], oacc[mt], 0, 0, 0);
+                };
+                auto ld_k = [&](sk_u32x4 (&o)[4], const int kk) __attribute__((always_inline)) {      // ks = 2 kk, 2 kk + 1; both tiles
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) o[i] = *(sk_lds_u4ptr)(kc[kk * 2 + (i >> 1)] + SK_SLOT_OFF(0, i & 1));
+                };
+                auto mm_k = [&](const sk_u32x4 (&o)[4], const int kk) __attribute__((always_inline)) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        sacc[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, o[i]), qreg[kk * 2 + (i >> 1)], sacc[i & 1], 0, 0, 0);
+                };
+                auto clear_scores = [&]() __attribute__((always_inline)) {
+#pragma unroll
+                    for (int t = 0; t < 2; ++t)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) sacc[t][v] = 0.f;
+                };
+#define SK_SB __builtin_amdgcn_sched_barrier(0)
+                sk_u32x4 o1[4], o2[4], o3[4], o4[4], o5[4], o6[4], o7[4];
+                if (KIND == 1) {
+                    ld_v(o1, 0, 1); ld_v(o2, 1, 0); SK_SB;
+                    mm_v(va0, 0, 0); SK_SB; ld_v(o3, 1, 1); SK_SB;
+                    mm_v(o1, 0, 1); SK_SB; ld_k(o4, 0); SK_SB;
+                    mm_v(o2, 1, 0); SK_SB; ld_k(o5, 1); SK_SB;
+                    mm_v(o3, 1, 1); SK_SB; ld_k(o6, 2); SK_SB;
+                    clear_scores(); mm_k(o4, 0); SK_SB; ld_k(o7, 3); SK_SB;
+                    mm_k(o5, 1); SK_SB;
+                    mm_k(o6, 2); SK_SB;
+                    mm_k(o7, 3);
+                } else if (KIND == 0) {
+                    ld_k(o4, 0); ld_k(o5, 1); ld_k(o6, 2); ld_k(o7, 3);
+                    clear_scores();
+                    mm_k(o4, 0); mm_k(o5, 1); mm_k(o6, 2); mm_k(o7, 3);
+                } else {
+                    ld_v(o1, 0, 1); ld_v(o2, 1, 0); ld_v(o3, 1, 1);
+                    mm_v(va0, 0, 0); mm_v(o1, 0, 1); mm_v(o2, 1, 0); mm_v(o3, 1, 1);
+                }
+#undef SK_SB
+            };
+            // Vector slot: softmax of iteration j, and the operands of the first group of matrix
+            // instructions of the slot that follows (V^T, first 16 keys of the iteration).
+            auto vector_slot = [&](const int j, const sk_lds_cptr (&vc)[4]) __attribute__((always_inline)) {
+#ifdef SK_EXPERIMENT
+                if (P.pad & 1) return;
+#endif
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt) va0[mt] = *(sk_lds_u4ptr)(vc[mt]);
+                step_softmax(j);
+            };
+            sk_lds_cptr kc[8];          // K operand addresses in the ring slot of the current iteration
+            sk_lds_cptr vc[4];          // V^T operand addresses in it (the next matrix slot reads them as "previous")
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) kc[ks] = kptr[ks];
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) vc[mt] = vptr[mt];
+            // slots of iteration 0 (ring slot 0): S only
+            sk_lds_barrier();
+            matrix_slot(sk_int<0>{}, 0, kc, vc);
+            if (grp == 1 && 1 < niter) wait_iteration(1);
+            sk_lds_barrier();
+            refill(0);
+            vector_slot(0, vc);
+#pragma unroll 1
+            for (int j = 1; j < niter; ++j) {
+                sk_lds_cptr vp[4];
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt) { vp[mt] = vc[mt]; vc[mt] = vptr[mt] + (j & 3) * 1024; }
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) kc[ks] = kptr[ks] + (j & 3) * 1024;
+                if (grp == 0) wait_iteration(j);
+                SK_STAMP();
+                    sk_lds_barrier();                                  // barrier 2j (group 0), 2j+1 (group 1)
+                SK_STAMP();
+                matrix_slot(sk_int<1>{}, j, kc, vp);
+                SK_STAMP();
+                if (grp == 1 && j + 1 < niter) wait_iteration(j + 1);
+                SK_STAMP();
+                sk_lds_barrier();                                  // barrier 2j+1 (group 0), 2j+2 (group 1)
+                SK_STAMP();
+                refill(j);
+                SK_STAMP();
+                vector_slot(j, vc);
+                SK_STAMP();
+            }
+            // slots after the last iteration: P V only
+            sk_lds_barrier();
+            matrix_slot(sk_int<2>{}, niter, kc, vc);
+            sk_lds_barrier();
+            if (grp == 0) sk_lds_barrier();      // the barrier group 1 took first
         }
     }
 
@@ -481,46 +693,55 @@ __global__ __launch_bounds__(256, SK_WGS_PER_CU) void sk_attn_bf16_d128(const sk
     // ---- epilogue: rows go out through LDS so that every store instruction writes whole rows ----
     // A lane holds 4-float pieces of ONE row (its accumulators are O^T); written as they are, a store
     // instruction would touch 64 different 128-byte lines.  Each wave transposes its 32 x 128 tile in
-    // its own 16 KiB of the (now idle) ring, XOR-swizzled by row so both directions are conflict-free.
+    // 16 KiB of the (now idle) ring, XOR-swizzled by row so both directions are conflict-free.  The
+    // ring holds four such tiles: with eight waves, waves 0-3 go first and waves 4-7 after them.
     if (NPH == 1) __syncthreads();                    // every wave is done reading key tiles
 #ifdef SK_EXPERIMENT
     if (P.pad & 8) return;                     // no output
 #endif
     const bool direct = w.part < 0;
-    const float inv = direct ? 1.0f / l_tot : 1.0f;
-    float* tr = (float*)lds + (NPH == 1 ? wave : rg * 2) * 4096;
+    auto emit = [&]() __attribute__((always_inline)) {
+        const float inv = direct ? 1.0f / l_tot : 1.0f;
+        float* tr = (float*)lds + (NPH == 1 ? (wave & 3) : rg * 2) * 4096;
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
+        for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            const int c4 = mt * 8 + q4 * 2 + kg;
-            *(float4*)(tr + r * 128 + ((c4 ^ r) & 31) * 4) =
-                make_float4(oacc[mt][q4 * 4 + 0] * inv, oacc[mt][q4 * 4 + 1] * inv, oacc[mt][q4 * 4 + 2] * inv, oacc[mt][q4 * 4 + 3] * inv);
-        }
-    const size_t orow_lane = ((size_t)(w.q_tok0 + tok_local) * P.g.Hq + hq);
-    if (row_valid && kg == 0) {
-        if (direct) { if (P.lse) P.lse[orow_lane] = (m_ref + sk_log2(l_tot)) * SK_LN2; }
-        else *(float2*)(P.part_ml + ((size_t)w.part * P.rows_per_slot + row_in_tile) * 2) = make_float2(m_ref, l_tot);
-    }
-    const int c4 = lane & 31;
-#pragma unroll
-    for (int it = 0; it < 16; ++it) {
-        const int row = it * 2 + (lane >> 5);
-        const float4 val = *(const float4*)(tr + row * 128 + ((c4 ^ row) & 31) * 4);
-        const int rit = rg * 32 + row;                 // row inside the tile
-        const int tok2 = rit >> log2G;
-        if (tok2 >= w.n_tok) continue;
-        if (direct) {
-            const size_t orow = ((size_t)(w.q_tok0 + tok2) * P.g.Hq + w.kv_head * G + (rit & (G - 1)));
-            if (P.out_dtype == 0) *(float4*)((float*)P.out + orow * 128 + c4 * 4) = val;
-            else {
-                const uint32_t lo = f32_to_bf16_bits(val.x) | ((uint32_t)f32_to_bf16_bits(val.y) << 16);
-                const uint32_t hi = f32_to_bf16_bits(val.z) | ((uint32_t)f32_to_bf16_bits(val.w) << 16);
-                *(uint2*)((uint16_t*)P.out + orow * 128 + c4 * 4) = make_uint2(lo, hi);
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int c4 = mt * 8 + q4 * 2 + kg;
+                *(float4*)(tr + r * 128 + ((c4 ^ r) & 31) * 4) =
+                    make_float4(oacc[mt][q4 * 4 + 0] * inv, oacc[mt][q4 * 4 + 1] * inv, oacc[mt][q4 * 4 + 2] * inv, oacc[mt][q4 * 4 + 3] * inv);
             }
-        } else {
-            *(float4*)(P.part_o + ((size_t)w.part * P.rows_per_slot + rit) * 128 + c4 * 4) = val;
+        const size_t orow_lane = ((size_t)(w.q_tok0 + tok_local) * P.g.Hq + hq);
+        if (row_valid && kg == 0) {
+            if (direct) { if (P.lse) P.lse[orow_lane] = (m_ref + sk_log2(l_tot)) * SK_LN2; }
+            else *(float2*)(P.part_ml + ((size_t)w.part * P.rows_per_slot + row_in_tile) * 2) = make_float2(m_ref, l_tot);
         }
+        const int c4 = lane & 31;
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+            const int row = it * 2 + (lane >> 5);
+            const float4 val = *(const float4*)(tr + row * 128 + ((c4 ^ row) & 31) * 4);
+            const int rit = rg * 32 + row;                 // row inside the tile
+            const int tok2 = rit >> log2G;
+            if (tok2 >= w.n_tok) continue;
+            if (direct) {
+                const size_t orow = ((size_t)(w.q_tok0 + tok2) * P.g.Hq + w.kv_head * G + (rit & (G - 1)));
+                if (P.out_dtype == 0) *(float4*)((float*)P.out + orow * 128 + c4 * 4) = val;
+                else {
+                    const uint32_t lo = f32_to_bf16_bits(val.x) | ((uint32_t)f32_to_bf16_bits(val.y) << 16);
+                    const uint32_t hi = f32_to_bf16_bits(val.z) | ((uint32_t)f32_to_bf16_bits(val.w) << 16);
+                    *(uint2*)((uint16_t*)P.out + orow * 128 + c4 * 4) = make_uint2(lo, hi);
+                }
+            } else {
+                *(float4*)(P.part_o + ((size_t)w.part * P.rows_per_slot + rit) * 128 + c4 * 4) = val;
+            }
+        }
+    };
+    if (NW == 4) emit();
+    else {
+        if (wave < 4) emit();
+        __syncthreads();
+        if (wave >= 4) emit();
     }
 }
 
@@ -856,8 +1077,11 @@ int sk_launch_attention(const sk_launch& L, int variant, int32_t n_workgroups, v
     if (n_workgroups <= 0) return 0;
     hipStream_t st = (hipStream_t)stream;
     switch (variant) {
-    case SK_KV_MFMA128: hipLaunchKernelGGL(sk_attn_bf16_d128<1>, dim3(n_workgroups), dim3(256), 0, st, L); break;
-    case SK_KV_MFMA64:  hipLaunchKernelGGL(sk_attn_bf16_d128<2>, dim3(n_workgroups), dim3(256), 0, st, L); break;
+    case SK_KV_MFMA256:      hipLaunchKernelGGL((sk_attn_bf16_d128<8, 1, 4>), dim3(n_workgroups), dim3(512), 0, st, L); break;
+    case SK_KV_MFMA128:      hipLaunchKernelGGL((sk_attn_bf16_d128<4, 1, 2>), dim3(n_workgroups), dim3(256), 0, st, L); break;
+    case SK_KV_MFMA64:       hipLaunchKernelGGL((sk_attn_bf16_d128<2, 2, 2>), dim3(n_workgroups), dim3(256), 0, st, L); break;
+    case SK_KV_MFMA128_DEEP: hipLaunchKernelGGL((sk_attn_bf16_d128<4, 1, 4>), dim3(n_workgroups), dim3(256), 0, st, L); break;
+    case SK_KV_MFMA64_DEEP:  hipLaunchKernelGGL((sk_attn_bf16_d128<2, 2, 4>), dim3(n_workgroups), dim3(256), 0, st, L); break;
     default:
         if (L.g.elem == 2) hipLaunchKernelGGL(sk_attn_simple<true>, dim3(n_workgroups), dim3(256), 0, st, L);
         else hipLaunchKernelGGL(sk_attn_simple<false>, dim3(n_workgroups), dim3(256), 0, st, L);

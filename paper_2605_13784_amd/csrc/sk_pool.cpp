@@ -172,14 +172,17 @@ hipEvent_t* prof_begin(sk_pool* p, hipStream_t st)
 // Which attention kernel takes a tile of `max_rows` query rows per KV head.
 struct Variant { int id; int rows_per_slot; int tok_per_tile; };
 
-bool pick_variant(const sk_pool* p, int64_t n_tok, Variant& v)
+// `one_per_cu`: the caller launches about one workgroup per CU (single-session calls), which
+// affords the 256-row tile and the 128 KiB key ring.
+bool pick_variant(const sk_pool* p, int64_t n_tok, Variant& v, bool one_per_cu = false)
 {
     const int G = p->L.G;
     const bool mfma_ok = p->d.dtype == SK_BF16 && p->d.head_dim == 128 && ilog2_exact(G) >= 0 && G <= 32;
     const char* force_simple = getenv("SK_FORCE_SIMPLE");
     if (mfma_ok && !(force_simple && force_simple[0] == '1')) {
-        if (n_tok * G > 64) { v.id = SK_KV_MFMA128; v.rows_per_slot = 128; v.tok_per_tile = 128 / G; }
-        else { v.id = SK_KV_MFMA64; v.rows_per_slot = 64; v.tok_per_tile = 64 / G; }
+        if (one_per_cu && n_tok * G > 128) { v.id = SK_KV_MFMA256; v.rows_per_slot = 256; v.tok_per_tile = 256 / G; }
+        else if (n_tok * G > 64) { v.id = one_per_cu ? SK_KV_MFMA128_DEEP : SK_KV_MFMA128; v.rows_per_slot = 128; v.tok_per_tile = 128 / G; }
+        else { v.id = one_per_cu ? SK_KV_MFMA64_DEEP : SK_KV_MFMA64; v.rows_per_slot = 64; v.tok_per_tile = 64 / G; }
         return true;
     }
     if (G > 16) return false;
@@ -206,7 +209,8 @@ int run_regular(sk_pool* p, int32_t id, const void* q, int64_t n_tok, int32_t po
                 int32_t n_splits_req, hipStream_t st)
 {
     Variant v;
-    if (!pick_variant(p, n_tok, v)) return SK_E_SHAPE;
+    const char* no256 = getenv("SK_NO_256");
+    if (!pick_variant(p, n_tok, v, !(no256 && no256[0] == '1'))) return SK_E_SHAPE;
     sk_launch L;
     fill_launch_common(p, L, q, out, out_dtype, lse, v);
     L.mode = SK_MODE_REGULAR;
@@ -225,7 +229,7 @@ int run_regular(sk_pool* p, int32_t id, const void* q, int64_t n_tok, int32_t po
         // A call with few row tiles (a query) is bound by streaming the cache once: one workgroup
         // per CU measured faster than two (fewer split partials to write and merge).  Calls with
         // many row tiles (appends) are bound by arithmetic and want two workgroups per CU.
-        const int64_t target = p->target_wgs_set ? p->target_wgs : (L.n_tiles <= 2 ? 256 : 512);
+        const int64_t target = p->target_wgs_set ? p->target_wgs : ((L.n_tiles <= 2 || v.id >= SK_KV_MFMA256) ? 256 : 512);
         S = std::max<int64_t>(1, (target + base_wgs / 2) / base_wgs);
     }
     int64_t chunk = kv_len > 0 ? (kv_len + S - 1) / S : 64;
@@ -246,6 +250,7 @@ int run_regular(sk_pool* p, int32_t id, const void* q, int64_t n_tok, int32_t po
     L.eph_blk[0] = 0; L.eph_cnt[0] = eph_cnt; L.eph_pos0[0] = eph_pos0;
 #ifdef SK_EXPERIMENT
     if (const char* x = getenv("SK_EXPERIMENT")) L.pad = atoi(x);
+    if (const char* x = getenv("SK_DEBUG_PTR")) L.work = (const sk_work*)strtoull(x, nullptr, 0);
 #endif
     const int32_t wgs = int32_t(base_wgs * parts);
     hipEvent_t* pe = prof_begin(p, st);
