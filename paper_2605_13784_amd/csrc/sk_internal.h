@@ -75,9 +75,8 @@ struct sk_scatter {
 };
 
 enum { SK_MODE_REGULAR = 0, SK_MODE_LIST = 1 };
-// attention kernel variants: fp32-FMA kernel; bf16 MFMA kernel with 128-, 64- and 256-row tiles;
-// the _DEEP ones keep a 128 KiB key ring (one workgroup per CU) instead of 64 KiB (two)
-enum { SK_KV_SIMPLE = 0, SK_KV_MFMA128 = 1, SK_KV_MFMA64 = 2, SK_KV_MFMA256 = 3, SK_KV_MFMA128_DEEP = 4, SK_KV_MFMA64_DEEP = 5 };
+// attention kernel variants: fp32-FMA kernel; bf16 MFMA kernel with 128-, 64- and 256-row tiles
+enum { SK_KV_SIMPLE = 0, SK_KV_MFMA128 = 1, SK_KV_MFMA64 = 2, SK_KV_MFMA256 = 3 };
 
 // Kernel argument block of the attention and combine kernels.
 struct sk_launch {

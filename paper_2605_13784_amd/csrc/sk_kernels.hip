@@ -167,17 +167,19 @@ __device__ __forceinline__ void sk_lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// One direct-to-LDS load of 16 bytes per lane: lane i's data lands at lds_addr + 16 i.
+// One direct-to-LDS load of 16 bytes per lane: lane i's data lands at lds_addr + IMM + 16 i.
 // Written as inline assembly so that the compiler's automatic wait insertion does not drain the
 // tiles in flight before every LDS read; the waits are placed by hand (SK_WAIT_VMCNT).
+template <unsigned IMM>
 __device__ __forceinline__ void sk_dma16(const void* base, unsigned lane_off, unsigned lds_addr)
 {   // address = base (scalar registers) + lane_off (one VGPR, unsigned)
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(lane_off), "s"(base) : "memory", "m0");
+    asm volatile("s_add_u32 m0, %0, %3\n\tglobal_load_lds_dwordx4 %1, %2"
+                 : : "s"(lds_addr), "v"(lane_off), "s"(base), "n"(IMM) : "memory", "m0", "scc");
 }
 
 // Pool blocks holding the two 16-key groups of the tile that starts at key t0 (scalar loads).
 // Groups past the end of the segment fall back to its last group.
-struct sk_tile_blocks { int32_t blk[2]; };
+struct sk_tile_blocks { uint32_t blk[2]; };
 __device__ __forceinline__ sk_tile_blocks sk_lookup_tile(const sk_seg& g, int t0, int last_group)
 {
     typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
@@ -186,33 +188,44 @@ __device__ __forceinline__ sk_tile_blocks sk_lookup_tile(const sk_seg& g, int t0
     for (int j = 0; j < 2; ++j) {
         int tg = t0 + 16 * j;
         tg = tg < last_group ? tg : last_group;
-        b.blk[j] = ((const_i32_ptr)(uintptr_t)g.table)[tg >> g.log2B];
+        b.blk[j] = (uint32_t)((const_i32_ptr)(uintptr_t)g.table)[(unsigned)tg >> g.log2B];
     }
     return b;
 }
 
-// Issues the four direct-to-LDS loads with which one of four waves (`sub` = 0..3) contributes to
-// one tile: a K and a V^T load for each of the tile's two 16-key groups.  The part of every source
-// address that depends on the lane is the same for all tiles of a segment (koff, voff); the rest
-// is uniform and stays in scalar registers.
+// Issues the four direct-to-LDS loads with which one of four waves contributes to one tile: a K
+// and a V^T load for each of the tile's two 16-key groups.  The address arithmetic per load is
+// kept short, because a wave issues it in between its vector or matrix work: the block's byte
+// offset is a shift (a block of this kernel holds B * 512 bytes per head), the lane-dependent
+// part of the address is one VGPR per kind of load, the same for every tile of a segment:
 //   K   : the wave fills LDS rows 16 j + 4 sub .. + 3 of group j; lane -> (row rr, chunk position),
 //         source chunk (position ^ rr):        koff = rr * 256 + ((lane & 15) ^ rr) * 16
 //   V^T : the wave fills dims 32 sub .. + 31 of group j; lane -> (dim dd, half position),
-//         source half (position ^ bit 3 of dd): voff = dd * 2B + (half ^ ((dd >> 3) & 1)) * 16
-// In LDS the sixteen 1 KiB units of a tile (K units 0-7, V^T units 8-15) lie `us` bytes apart, with
-// the same unit of the other tiles of the ring in between; `tile_addr` is the address of unit 0.
-__device__ __forceinline__ void sk_issue_tile(const sk_seg& g, int t0, int last_group, const sk_tile_blocks& tb,
-                                              unsigned tile_addr, unsigned us, int sub, unsigned koff, unsigned voff)
+//         source half (position ^ bit 3 of dd): voff = V offset in the block + dd * 2B + (half ^ ((dd >> 3) & 1)) * 16
+// and the 16-key group's offset inside a block of more than 16 tokens is added to those.
+// In LDS the sixteen 1 KiB units of a tile (K units 0-7, V^T units 8-15) lie US bytes apart, with
+// the same unit of the other tiles of the ring in between; `unit_addr` is the address of unit `sub`.
+template <unsigned US, int J>
+__device__ __forceinline__ void sk_issue_group(const sk_seg& g, int t0, int last_group, uint32_t blk,
+                                               unsigned unit_addr, unsigned koff, unsigned voff)
 {
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {            // j = 16-key group of the tile
-        int tg = t0 + 16 * j;
-        tg = tg < last_group ? tg : last_group;
-        const unsigned char* bb = g.base + (int64_t)tb.blk[j] * g.blk_stride;
-        const int slot0 = tg & (g.B - 1);
-        sk_dma16(bb + (size_t)slot0 * 256, koff, tile_addr + (j * 4 + sub) * us);
-        sk_dma16(bb + g.v_off + slot0 * 2, voff, tile_addr + (8 + j * 4 + sub) * us);
+    int tg = t0 + 16 * J;
+    tg = tg < last_group ? tg : last_group;
+    const unsigned char* bb = g.base + ((uint64_t)blk << (g.log2B + 9));
+    if (g.B > 16) {
+        const unsigned slot0 = (unsigned)tg & (unsigned)(g.B - 1);
+        koff += slot0 << 8;
+        voff += slot0 << 1;
     }
+    sk_dma16<J * 4 * US>(bb, koff, unit_addr);
+    sk_dma16<(8 + J * 4) * US>(bb, voff, unit_addr);
+}
+template <unsigned US>
+__device__ __forceinline__ void sk_issue_tile(const sk_seg& g, int t0, int last_group, const sk_tile_blocks& tb,
+                                              unsigned unit_addr, unsigned koff, unsigned voff)
+{
+    sk_issue_group<US, 0>(g, t0, last_group, tb.blk[0], unit_addr, koff, voff);
+    sk_issue_group<US, 1>(g, t0, last_group, tb.blk[1], unit_addr, koff, voff);
 }
 
 #ifdef SK_EXPERIMENT              // development builds: P.pad bit 0 = no arithmetic, bit 1 = no loads
@@ -249,6 +262,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
     const unsigned lds_base = (unsigned)(uintptr_t)(sk_lds_ptr)lds;   // LDS byte address of the ring
 #ifdef SK_EXPERIMENT
     int stamp_n = 0;
+    if ((P.pad & 64) && blockIdx.x == 0 && threadIdx.x == 0) { ((long long*)P.work)[2048] = clock64(); ((long long*)P.work)[2049] = wall_clock64(); }
 #endif
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // in a scalar register
@@ -263,6 +277,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
     const int grp = NW == 8 ? (wave >> 2) : 0;
     const int sub = wave & 3;
 #endif
+    const unsigned unit_base = lds_base + sub * US;                // LDS address of this wave's unit of ring slot 0, tile 0
     const int r = lane & 31, kg = lane >> 5;
     const int log2G = P.g.log2G, G = P.g.G;
     const int row_in_tile = rg * 32 + r;
@@ -332,7 +347,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
         // lane-dependent parts of the DMA source addresses for this segment
         const unsigned koff = (unsigned)((sub * 4 + (lane >> 4)) * 256 + (((lane & 15) ^ (sub * 4 + (lane >> 4))) << 4));
         const int vdd = sub * 32 + (lane >> 1);
-        const unsigned voff = (unsigned)(vdd * (2 * g.B) + ((((lane & 1) ^ ((vdd >> 3) & 1))) << 4));
+        const unsigned voff = (unsigned)(g.v_off + vdd * (2 * g.B) + ((((lane & 1) ^ ((vdd >> 3) & 1))) << 4));
 
         // ---- the three steps of one iteration (64 keys) for this wave; the ring slot is a
         // compile-time constant so that it folds into the offset field of the LDS instructions ----
@@ -455,7 +470,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
                     for (int p = 0; p < TPI; ++p) {
                         const int t0 = g.begin + (a * TPI + p) * SK_TILE;
                         const sk_tile_blocks tb = sk_lookup_tile(g, t0, last_group);
-                        SK_EXP_LOADS sk_issue_tile(g, t0, last_group, tb, lds_base + SK_SLOT_OFF(a, p), US, sub, koff, voff);
+                        SK_EXP_LOADS sk_issue_tile<US>(g, t0, last_group, tb, unit_base + SK_SLOT_OFF(a, p), koff, voff);
                     }
                 }
             }
@@ -475,12 +490,19 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
                 if (NSS == 2 || later <= 0) SK_WAIT_VMCNT(0);
                 else if (later == 1) SK_WAIT_VMCNT(LPW);
                 else SK_WAIT_VMCNT(2 * LPW);
+#ifdef SK_EXPERIMENT
+                if (!(P.pad & 128))                 // bit 7: no barrier in the loop
+#endif
                 sk_lds_barrier();
-                if (it + NSS - 1 < niter) {
+                bool do_refill = it + NSS - 1 < niter;
+#ifdef SK_EXPERIMENT
+                if (P.pad & 256) do_refill = false;     // bit 8: no refill code at all (addresses, table lookups)
+#endif
+                if (do_refill) {
 #pragma unroll
                     for (int p = 0; p < TPI; ++p)
-                        SK_EXP_LOADS sk_issue_tile(g, g.begin + ((it + NSS - 1) * TPI + p) * SK_TILE, last_group, nb[p],
-                                                   lds_base + SK_SLOT_OFF((STAGE + NSS - 1) % NSS, p), US, sub, koff, voff);
+                        SK_EXP_LOADS sk_issue_tile<US>(g, g.begin + ((it + NSS - 1) * TPI + p) * SK_TILE, last_group, nb[p],
+                                                       unit_base + SK_SLOT_OFF((STAGE + NSS - 1) % NSS, p), koff, voff);
                     if (it + NSS < niter) {
 #pragma unroll
                         for (int p = 0; p < TPI; ++p)
@@ -530,7 +552,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
                 if (a < ahead && a < niter) {
                     const int t0 = g.begin + (a * TPI + my_tile) * SK_TILE;
                     const sk_tile_blocks tb = sk_lookup_tile(g, t0, last_group);
-                    SK_EXP_LOADS sk_issue_tile(g, t0, last_group, tb, lds_base + SK_SLOT_OFF(a, my_tile), US, sub, koff, voff);
+                    SK_EXP_LOADS sk_issue_tile<US>(g, t0, last_group, tb, unit_base + SK_SLOT_OFF(a, my_tile), koff, voff);
                 }
             }
             sk_tile_blocks nb = sk_lookup_tile(g, g.begin + (ahead * TPI + my_tile) * SK_TILE, last_group);
@@ -546,8 +568,8 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
             auto refill = [&](const int j) __attribute__((always_inline)) {
                 const int i = j + ahead;
                 if (i < niter) {
-                    SK_EXP_LOADS sk_issue_tile(g, g.begin + (i * TPI + my_tile) * SK_TILE, last_group, nb,
-                                               lds_base + SK_SLOT_OFF(i & 3, my_tile), US, sub, koff, voff);
+                    SK_EXP_LOADS sk_issue_tile<US>(g, g.begin + (i * TPI + my_tile) * SK_TILE, last_group, nb,
+                                                   unit_base + SK_SLOT_OFF(i & 3, my_tile), koff, voff);
                     if (i + 1 < niter) nb = sk_lookup_tile(g, g.begin + ((i + 1) * TPI + my_tile) * SK_TILE, last_group);
                 }
             };
@@ -662,6 +684,9 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
         }
     }
 
+#ifdef SK_EXPERIMENT
+    if ((P.pad & 64) && blockIdx.x == 0 && threadIdx.x == 0) { ((long long*)P.work)[2050] = clock64(); ((long long*)P.work)[2051] = wall_clock64(); }
+#endif
     float l_tot = l_run + __shfl_xor(l_run, 32, 64);
 
     if (NPH > 1) {
@@ -1080,8 +1105,6 @@ int sk_launch_attention(const sk_launch& L, int variant, int32_t n_workgroups, v
     case SK_KV_MFMA256:      hipLaunchKernelGGL((sk_attn_bf16_d128<8, 1, 4>), dim3(n_workgroups), dim3(512), 0, st, L); break;
     case SK_KV_MFMA128:      hipLaunchKernelGGL((sk_attn_bf16_d128<4, 1, 2>), dim3(n_workgroups), dim3(256), 0, st, L); break;
     case SK_KV_MFMA64:       hipLaunchKernelGGL((sk_attn_bf16_d128<2, 2, 2>), dim3(n_workgroups), dim3(256), 0, st, L); break;
-    case SK_KV_MFMA128_DEEP: hipLaunchKernelGGL((sk_attn_bf16_d128<4, 1, 4>), dim3(n_workgroups), dim3(256), 0, st, L); break;
-    case SK_KV_MFMA64_DEEP:  hipLaunchKernelGGL((sk_attn_bf16_d128<2, 2, 4>), dim3(n_workgroups), dim3(256), 0, st, L); break;
     default:
         if (L.g.elem == 2) hipLaunchKernelGGL(sk_attn_simple<true>, dim3(n_workgroups), dim3(256), 0, st, L);
         else hipLaunchKernelGGL(sk_attn_simple<false>, dim3(n_workgroups), dim3(256), 0, st, L);

@@ -172,17 +172,17 @@ hipEvent_t* prof_begin(sk_pool* p, hipStream_t st)
 // Which attention kernel takes a tile of `max_rows` query rows per KV head.
 struct Variant { int id; int rows_per_slot; int tok_per_tile; };
 
-// `one_per_cu`: the caller launches about one workgroup per CU (single-session calls), which
-// affords the 256-row tile and the 128 KiB key ring.
-bool pick_variant(const sk_pool* p, int64_t n_tok, Variant& v, bool one_per_cu = false)
+// `allow_256`: the caller can launch one workgroup per CU (single-session calls), which the
+// 256-row tile with its 128 KiB key ring needs.
+bool pick_variant(const sk_pool* p, int64_t n_tok, Variant& v, bool allow_256 = false)
 {
     const int G = p->L.G;
     const bool mfma_ok = p->d.dtype == SK_BF16 && p->d.head_dim == 128 && ilog2_exact(G) >= 0 && G <= 32;
     const char* force_simple = getenv("SK_FORCE_SIMPLE");
     if (mfma_ok && !(force_simple && force_simple[0] == '1')) {
-        if (one_per_cu && n_tok * G > 128) { v.id = SK_KV_MFMA256; v.rows_per_slot = 256; v.tok_per_tile = 256 / G; }
-        else if (n_tok * G > 64) { v.id = one_per_cu ? SK_KV_MFMA128_DEEP : SK_KV_MFMA128; v.rows_per_slot = 128; v.tok_per_tile = 128 / G; }
-        else { v.id = one_per_cu ? SK_KV_MFMA64_DEEP : SK_KV_MFMA64; v.rows_per_slot = 64; v.tok_per_tile = 64 / G; }
+        if (allow_256 && n_tok * G > 128) { v.id = SK_KV_MFMA256; v.rows_per_slot = 256; v.tok_per_tile = 256 / G; }
+        else if (n_tok * G > 64) { v.id = SK_KV_MFMA128; v.rows_per_slot = 128; v.tok_per_tile = 128 / G; }
+        else { v.id = SK_KV_MFMA64; v.rows_per_slot = 64; v.tok_per_tile = 64 / G; }
         return true;
     }
     if (G > 16) return false;
@@ -229,7 +229,7 @@ int run_regular(sk_pool* p, int32_t id, const void* q, int64_t n_tok, int32_t po
         // A call with few row tiles (a query) is bound by streaming the cache once: one workgroup
         // per CU measured faster than two (fewer split partials to write and merge).  Calls with
         // many row tiles (appends) are bound by arithmetic and want two workgroups per CU.
-        const int64_t target = p->target_wgs_set ? p->target_wgs : ((L.n_tiles <= 2 || v.id >= SK_KV_MFMA256) ? 256 : 512);
+        const int64_t target = p->target_wgs_set ? p->target_wgs : ((L.n_tiles <= 2 || v.id == SK_KV_MFMA256) ? 256 : 512);
         S = std::max<int64_t>(1, (target + base_wgs / 2) / base_wgs);
     }
     int64_t chunk = kv_len > 0 ? (kv_len + S - 1) / S : 64;
