@@ -17,6 +17,15 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 __device__ __forceinline__ float sk_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float sk_log2(float x) { return __builtin_amdgcn_logf(x); }
 
+// Value of lane (i ^ 32) next to the lane's own, with one v_permlane32_swap (no LDS round trip):
+// swapping a register with a copy of itself leaves {x[i % 32], x[i % 32 + 32]} in every lane.
+struct sk_halves { float lo, hi; };
+__device__ __forceinline__ sk_halves sk_both_halves(float x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return sk_halves{__uint_as_float(r[0]), __uint_as_float(r[1])};
+}
+
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
 {   // round to nearest even; NaN stays NaN
@@ -421,7 +430,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
 #pragma unroll
                     for (int v = 0; v < 16; ++v) mt_ = fmaxf(mt_, sacc[t][v]);
             }
-            mt_ = fmaxf(mt_, __shfl_xor(mt_, 32, 64)) * c_scale;      // log2 units (c_scale > 0)
+            { const sk_halves h = sk_both_halves(mt_); mt_ = fmaxf(h.lo, h.hi) * c_scale; }      // log2 units (c_scale > 0)
             const bool raise = mt_ > m_ref + SK_RESCALE_SLACK;
             if (__any(raise)) {
                 const float alpha = raise ? sk_exp2(m_ref - mt_) : 1.0f;
@@ -687,7 +696,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
 #ifdef SK_EXPERIMENT
     if ((P.pad & 64) && blockIdx.x == 0 && threadIdx.x == 0) { ((long long*)P.work)[2050] = clock64(); ((long long*)P.work)[2051] = wall_clock64(); }
 #endif
-    float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    float l_tot; { const sk_halves h = sk_both_halves(l_run); l_tot = h.lo + h.hi; }
 
     if (NPH > 1) {
         // merge the key phases of each row group through LDS: [value index][lane], value 64 = m, 65 = l
