@@ -363,8 +363,11 @@ void add_tiles(ListGroup& g, const TileReq& base, int32_t q_row0, int32_t T)
     }
 }
 
+constexpr int kMaxGroups = 3;   // one launch per kernel variant in use
+
 int run_list(sk_pool* p, ScatterBatch* sb, int n_sb, ListGroup* groups, int n_groups, int out_dtype, hipStream_t st)
 {
+    if (n_groups > kMaxGroups) return SK_E_INVAL;
     const int Hkv = p->d.n_kv_heads;
     int64_t kv_total = 0, n_tiles = 0;
     for (int gi = 0; gi < n_groups; ++gi)
@@ -375,9 +378,9 @@ int run_list(sk_pool* p, ScatterBatch* sb, int n_sb, ListGroup* groups, int n_gr
     int64_t chunk = std::max<int64_t>(256, (kv_total * Hkv + target - 1) / target);
     chunk = (chunk + 63) / 64 * 64;
     const int64_t cap_rows = p->L.part_slots * kPartSlotRows;
-    std::vector<sk_work> work[2];
-    std::vector<sk_comb> comb[2];
-    int64_t rows_base[2] = {0, 0};
+    std::vector<sk_work> work[kMaxGroups];
+    std::vector<sk_comb> comb[kMaxGroups];
+    int64_t rows_base[kMaxGroups] = {};
     for (;;) {
         int64_t rows_used = 0;
         bool ok = true;
@@ -444,7 +447,7 @@ int run_list(sk_pool* p, ScatterBatch* sb, int n_sb, ListGroup* groups, int n_gr
     if (rc) return rc;
     unsigned char* ws = (unsigned char*)p->d.workspace;
     unsigned char* dev_meta = ws + p->L.off_meta;
-    size_t off = 0, off_sb[2] = {0, 0}, off_work[2] = {0, 0}, off_comb[2] = {0, 0};
+    size_t off = 0, off_sb[2] = {0, 0}, off_work[kMaxGroups] = {}, off_comb[kMaxGroups] = {};
     for (int i = 0; i < n_sb; ++i) {
         off_sb[i] = off;
         memcpy(host + off, sb[i].items.data(), sb[i].items.size() * sizeof(sk_scatter));
@@ -468,7 +471,7 @@ int run_list(sk_pool* p, ScatterBatch* sb, int n_sb, ListGroup* groups, int n_gr
         p->stats.launches++;
     }
     hipEvent_t* pe = prof_begin(p, st);
-    sk_launch L[2];
+    sk_launch L[kMaxGroups];
     int32_t wgs = 0, max_parts = 1;
     for (int gi = 0; gi < n_groups; ++gi) {
         if (work[gi].empty()) continue;
@@ -495,7 +498,8 @@ int run_list(sk_pool* p, ScatterBatch* sb, int n_sb, ListGroup* groups, int n_gr
     if (pe) (void)hipEventRecord(pe[2], st);
     p->stats.kv_bytes_streamed += kv_total * 2 * Hkv * p->d.head_dim * p->L.elem;
     p->last.workgroups = wgs; p->last.n_splits = max_parts; p->last.row_tiles = (int32_t)n_tiles;
-    p->last.kernel_variant = groups[0].tiles.empty() ? groups[n_groups - 1].v.id : groups[0].v.id;
+    p->last.kernel_variant = groups[0].v.id;
+    for (int gi = n_groups - 1; gi >= 0; --gi) if (!groups[gi].tiles.empty()) p->last.kernel_variant = groups[gi].v.id;
     return SK_OK;
 }
 
@@ -750,7 +754,9 @@ int sk_batch_step(sk_pool* p, int32_t n_items, const int32_t* session_id, const 
     // nothing below fails for lack of pool resources
     ScatterBatch sb;
     sb.k = k; sb.v = v;
-    ListGroup groups[2];
+    ListGroup groups[3];
+    const char* no256 = getenv("SK_NO_256");
+    const bool allow_256 = !(no256 && no256[0] == '1');
     int64_t eph_cursor = 0;
     for (int i = 0; i < n_items; ++i) {
         Session* s = get_session(p, session_id[i]);
@@ -781,14 +787,16 @@ int sk_batch_step(sk_pool* p, int32_t n_items, const int32_t* session_id, const 
                 base.pos0 = SK_NO_CAUSAL; base.kv_vis = (int32_t)n;
             }
         }
+        // items of more than 128 rows per KV head (the appends) go to the 256-row kernel, which is
+        // launched first; then the 128-row items, then the small ones
         Variant vv;
-        pick_variant(p, T, vv);
-        ListGroup& g = groups[vv.id == SK_KV_MFMA64 ? 1 : 0];
+        pick_variant(p, T, vv, allow_256);
+        ListGroup& g = groups[vv.id == SK_KV_MFMA64 ? 2 : vv.id == SK_KV_MFMA128 ? 1 : 0];
         g.v = vv; g.q = q; g.out = out; g.lse = lse;
         add_tiles(g, base, cu_tokens[i], T);
     }
     if (!p->device) return SK_OK;
-    return run_list(p, &sb, 1, groups, 2, out_dtype, (hipStream_t)hip_stream);
+    return run_list(p, &sb, 1, groups, 3, out_dtype, (hipStream_t)hip_stream);
 }
 
 int sk_session_query_shared_prefix(sk_pool* p, int32_t id, const void* qp, const void* kp, const void* vp, int32_t P,
