@@ -35,8 +35,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # Keyed by (workload, block_tokens, cache state); other configurations report null.
 MEASURED_HBM_TRAFFIC = {
     ("cfg2_llama3_8b_layer_32k", 16, "cold"): {
-        "query": {"fetch_bytes": 134.95e6, "write_bytes": 17.04e6, "total_bytes": 151.99e6},
-        "append": {"fetch_bytes": 136.77e6, "write_bytes": 34.08e6, "total_bytes": 170.85e6},
+        "query": {"fetch_bytes": 134.94e6, "write_bytes": 17.04e6, "total_bytes": 151.98e6},
+        "append": {"fetch_bytes": 136.93e6, "write_bytes": 34.08e6, "total_bytes": 171.01e6},
     },
 }
 
