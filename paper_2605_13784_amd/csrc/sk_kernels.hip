@@ -120,19 +120,21 @@ __device__ __forceinline__ const unsigned char* sk_group_base(const sk_seg& g, i
 // ---------------------------------------------------------------------------------------------
 // bf16 MFMA attention kernel, head_dim 128.
 //
-// Workgroup = 4 waves, arranged as NRG row groups x NPH key phases (NRG * NPH = 4): a row group
-// owns 32 query rows, a phase owns every NPH-th key tile.
+// Workgroup = NRG row groups x NPH key phases = 4 or 8 waves: a row group owns 32 query rows, a
+// phase owns every NPH-th key tile.  Instances: <4,1,2> 128-row tile; <2,2,2> 64-row tile, the two
+// phases merged through LDS at the end; <8,1,4> 256-row tile, eight waves in two groups that take
+// turns on the matrix pipe and the vector ALU (described at the segment loop).
 //
 // Keys move HBM -> LDS with direct-to-LDS loads (global_load_lds_dwordx4), never through
-// registers, into a ring of four 32-key tiles (K 8 KiB + V^T 8 KiB each).  One iteration
-// consumes two tiles (64 keys: both by every wave when NPH = 1, one per phase when NPH = 2)
-// while the other two are in flight, 32 KiB per workgroup and 64 KiB per CU, which is what
-// covers the HBM latency.  A direct-to-LDS load writes lane i's 16 bytes at
+// registers, into a ring of NSS iterations of two 32-key tiles (K 8 KiB + V^T 8 KiB each): 64 KiB
+// with two workgroups per CU, or 128 KiB with one.  One iteration consumes two tiles (64 keys:
+// both by every wave when NPH = 1, one per phase when NPH = 2) while the others are in flight,
+// which is what covers the HBM latency.  A direct-to-LDS load writes lane i's 16 bytes at
 // base + 16 i, so the bank swizzle is applied to the *source* address each lane picks:
 //   K   : LDS row rho holds global 16-byte chunk (c ^ (rho & 15)) at chunk position c,
 //   V^T : LDS row dd of a 16-key group holds the two 8-key halves swapped when bit 3 of dd is set.
-// The loads of one tile are issued by all four waves (4 instructions each); a wave waits on its
-// own vmcnt and a workgroup barrier publishes the tile.  Nothing else in the loop is a vector
+// The sixteen loads of one tile are issued by four waves (4 instructions each); a wave waits on
+// its own vmcnt and a workgroup barrier publishes the tile.  Nothing else in the loop is a vector
 // memory instruction (block-table entries are scalar loads), so the outstanding-load count a
 // wave waits for is exact.
 // Tiles past the end of a segment re-read its last 16-key group (always valid memory); their
@@ -143,7 +145,7 @@ __device__ __forceinline__ const unsigned char* sk_group_base(const sk_seg& g, i
 //   S^T[32 keys][32 rows]  = K[32][128] * Q^T[128][32]        8 x mfma_f32_32x32x16_bf16
 //   O^T[128][32 rows]     += V^T[128][32 keys] * P^T[32][32]  8 x mfma_f32_32x32x16_bf16
 // With S transposed a lane owns one query row (lane % 32) and 16 keys of it, so the row maximum
-// and sum need one cross-lane exchange (lane ^ 32) and P feeds the second contraction straight
+// and sum need one cross-lane exchange (lane ^ 32, v_permlane32_swap) and P feeds the second contraction straight
 // from registers.  Key row rho of the first product is loaded from key tau(rho) (bits 2 and 3
 // swapped) so that the 8 P values a lane hands to one PV instruction belong to 8 consecutive
 // keys, which are one 16-byte read of V^T.
