@@ -110,7 +110,7 @@ def main():
     ap.add_argument("--hot", action="store_true", help="one session only: K/V may stay in the last-level cache")
     ap.add_argument("--n-splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extras", action="store_true", help="skip the other workloads (128K context, question batch, multi-tenant step)")
+    ap.add_argument("--no-extras", action="store_true", help="skip the other workloads (128K context, question batch, multi-tenant step, sliding window)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy three times before the steps (a kernel of known "
                          "size against which hardware byte counters are scaled)")
@@ -144,6 +144,7 @@ def main():
         extras[other] = {k: r[k] for k in ("ms_per_step", "query", "append", "roofline_query", "roofline_append")}
         extras["cfg5_question_batch_64k"] = question_batch(sk)
         extras["cfg4_multi_tenant_step"] = multi_tenant(sk)
+        extras["sliding_window_32k"] = sliding_window(sk)
         res["extras"] = extras
     if not args.no_cpu_baseline:
         rows = args.cpu_rows or ((L + nq) * shape.n_q_heads if n <= 32768 else 4096)
@@ -238,6 +239,53 @@ def stream_workload(sk, name, args, steps, warmup, calibrate=False):
                    "tflops": af / (a_total_us * 1e-6) / 1e12, "mfma_frac": af / (a_total_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
         "roofline": roof_a if a_kernel_us >= q_kernel_us else roof_q, "roofline_query": roof_q, "roofline_append": roof_a,
     }
+
+
+def sliding_window(sk, cap=32768, n_frozen=500, L=256, nq=32, n_sessions=9, steps=40):
+    """The stream step of the headline workload on sessions that stay at `cap` retained tokens:
+    evict the L oldest tokens behind a frozen prefix, append L, query (Alg. 1 with a full Region 1).
+    Nothing is truncated back; the sessions really slide."""
+    shape = synth.CFG2
+    B = 16
+    n_blocks = n_sessions * (cap // B + 8) + 64
+    pool = sk.Pool(shape.dtype, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, B, n_blocks,
+                   max_sessions=n_sessions, max_batch_tokens=1024)
+    gen = synth.generator(2, stream=40)
+    sids = build_sessions(pool, shape, cap, 1024, n_sessions, gen)
+    for sid in sids:
+        pool.sk_session_freeze(sid, n_frozen)
+    qa, ka, va = [t.cuda() for t in synth.draw_qkv(gen, L, shape)]
+    qq = synth.draw(gen, (nq, shape.n_q_heads, shape.head_dim), shape.dtype).cuda()
+    out_a = torch.empty((L, shape.n_q_heads, shape.head_dim), dtype=torch.float32, device="cuda")
+    out_q = torch.empty((nq, shape.n_q_heads, shape.head_dim), dtype=torch.float32, device="cuda")
+    lse_a = torch.empty((L, shape.n_q_heads), dtype=torch.float32, device="cuda")
+    lse_q = torch.empty((nq, shape.n_q_heads), dtype=torch.float32, device="cuda")
+    evict_host_s = 0.0
+
+    def step(i):
+        nonlocal evict_host_s
+        sid = sids[i % n_sessions]
+        t = time.perf_counter()
+        pool.sk_session_evict_oldest(sid, L)
+        evict_host_s += time.perf_counter() - t
+        pool.sk_session_append(sid, qa, ka, va, out=out_a, lse=lse_a)
+        pool.sk_session_query(sid, qq, out=out_q, lse=lse_q)
+
+    for i in range(2 * n_sessions):
+        step(i)
+    torch.cuda.synchronize()
+    evict_host_s = 0.0
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(2 * n_sessions + i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    length = pool.sk_session_length(sids[0])
+    blocks = len(pool.sk_session_block_table(sids[0]))
+    pool.close()
+    return {"retained_tokens": int(length), "frozen_tokens": n_frozen, "evict_append_query_ms_per_step": wall * 1e3 / steps,
+            "tokens_per_s": (L + nq) * steps / wall, "evict_call_host_us_incl_wait_for_upload_slot": evict_host_s * 1e6 / steps,
+            "blocks_per_session": blocks, "block_table_bytes_copied_per_evict": (blocks - (n_frozen + B - 1) // B) * 4}
 
 
 def question_batch(sk, n=65536, L=256, P=16, NQ=64, Sfx=8, cycles=8):

@@ -171,20 +171,38 @@ int sk_session_query_shared_prefix(sk_pool* pool, int32_t id,
 
 /*
  * Reads a session's committed K/V back in token order: k_out, v_out [count][Hkv][d] DEVICE,
- * pool dtype, tokens first..first+count-1.  Bit copy through the block table (used to check
- * the commit and to export a session).
+ * pool dtype, retained tokens first..first+count-1 (evicted tokens do not count).  Bit copy
+ * through the block table (used to check the commit and to export a session).
  */
 int sk_session_gather(const sk_pool* pool, int32_t id, int64_t first, int64_t count,
                       void* k_out, void* v_out, void* hip_stream);
 
 /*
- * Drops every cached token at position >= new_length: the SeqRemove(s, p, infinity) of
- * Sec. 3.9.3 / Alg. 3, by which a caller can also reproduce the literal Strip / Extend / Clear
- * cycle (append, read the output, truncate).  Host metadata only: whole blocks past the new
- * end return to the free list, no device work, kv_mem bytes are not touched.
- * new_length > current length gives SK_E_INVAL.
+ * Drops every cached token behind the first new_length retained ones: the
+ * SeqRemove(s, p, infinity) of Sec. 3.9.3 / Alg. 3, by which a caller can also reproduce the
+ * literal Strip / Extend / Clear cycle (append, read the output, truncate).  Host metadata only:
+ * whole blocks past the new end return to the free list, no device work, kv_mem bytes are not
+ * touched.  new_length > current length gives SK_E_INVAL.
  */
 int sk_session_truncate(sk_pool* pool, int32_t id, int64_t new_length);
+
+/*
+ * REGION 0 / REGION 1 (Sec. 3.3; Alg. 1 "if size + |tokens| > capacity: evict_oldest").
+ * sk_session_freeze marks the first n_frozen tokens of the session as Region 0: they are never
+ * evicted.  n_frozen may only grow, must not exceed the session's length, and cannot change once
+ * tokens have been evicted behind it (SK_E_INVAL).
+ * sk_session_evict_oldest removes the n_tokens oldest tokens that are not frozen (FIFO eviction
+ * of the sliding Region 1); more than the session holds there gives SK_E_INVAL and changes
+ * nothing.  Attention then runs over [Region 0 ; what is left of Region 1]; the order of the
+ * retained tokens is kept, and sk_session_length / gather / truncate count retained tokens only.
+ * Re-encoding positions after an eviction is the caller's concern (as for every K the cache is
+ * given).  Metadata only: blocks that hold nothing but evicted tokens return to the free list at
+ * once; evicted tokens that share a block with retained ones stay in kv_mem and are skipped by
+ * the kernels.  The only device work is a copy of the moved part of the session's block table,
+ * ordered on hip_stream (which must be the stream of the session's other calls).
+ */
+int sk_session_freeze(sk_pool* pool, int32_t id, int64_t n_frozen);
+int sk_session_evict_oldest(sk_pool* pool, int32_t id, int64_t n_tokens, void* hip_stream);
 
 /* Byte offset inside kv_mem of element (block, kv_head, is_v, slot, dim), so a harness can
  * address the pool without knowing the layout.  Negative on bad arguments. */
@@ -192,9 +210,9 @@ int64_t sk_pool_element_offset(const sk_pool* pool, int64_t block, int32_t kv_he
                                int32_t slot, int32_t dim);
 
 /* Counters since creation: tokens appended, query tokens, kernel launches, cached-token
- * bytes the attention kernels were asked to stream. */
+ * bytes the attention kernels were asked to stream, tokens evicted. */
 typedef struct sk_pool_stats {
-    int64_t tokens_appended, tokens_queried, launches, kv_bytes_streamed;
+    int64_t tokens_appended, tokens_queried, launches, kv_bytes_streamed, tokens_evicted;
 } sk_pool_stats;
 int sk_pool_get_stats(const sk_pool* pool, sk_pool_stats* out);
 

@@ -103,6 +103,23 @@ class OracleSession:
         npdt = _DT[dtype][1]
         self.K = np.zeros((0, n_kv_heads, head_dim), dtype=npdt)
         self.V = np.zeros((0, n_kv_heads, head_dim), dtype=npdt)
+        self.n_frozen = 0
+
+    def freeze(self, n_frozen):
+        """Region 0 (Sec. 3.3): the first n_frozen tokens are never evicted."""
+        if not (self.n_frozen <= n_frozen <= self.length):
+            raise ValueError("n_frozen")
+        self.n_frozen = int(n_frozen)
+
+    def evict_oldest(self, n_tokens):
+        """Region-1 FIFO eviction (Sec. 3.3; Alg. 1 evict_oldest): the n_tokens oldest tokens behind
+        the frozen region leave the cache; attention over them is lost (Sec. 5.3 discussion of the
+        sliding window), the order of the rest is kept."""
+        if not (0 <= n_tokens <= self.length - self.n_frozen):
+            raise ValueError("n_tokens")
+        a, b = self.n_frozen, self.n_frozen + int(n_tokens)
+        self.K = np.concatenate([self.K[:a], self.K[b:]], axis=0)
+        self.V = np.concatenate([self.V[:a], self.V[b:]], axis=0)
 
     @property
     def length(self):
@@ -162,6 +179,7 @@ class OracleSession:
             raise ValueError("new_length out of range")
         self.K = self.K[:new_length].copy()
         self.V = self.V[:new_length].copy()
+        self.n_frozen = min(self.n_frozen, int(new_length))
 
     def cache(self):
         """Copies of the committed keys and values, [n,Hkv,d] raw bits."""

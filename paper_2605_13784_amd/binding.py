@@ -42,7 +42,8 @@ class sk_pool_desc(ctypes.Structure):
 
 class sk_pool_stats(ctypes.Structure):
     _fields_ = [("tokens_appended", ctypes.c_int64), ("tokens_queried", ctypes.c_int64),
-                ("launches", ctypes.c_int64), ("kv_bytes_streamed", ctypes.c_int64)]
+                ("launches", ctypes.c_int64), ("kv_bytes_streamed", ctypes.c_int64),
+                ("tokens_evicted", ctypes.c_int64)]
 
 
 class sk_launch_info(ctypes.Structure):
@@ -59,7 +60,8 @@ EXPORTS = [
     "sk_pool_blocks_free", "sk_pool_set_alloc_order", "sk_session_create", "sk_session_destroy",
     "sk_session_length", "sk_session_block_table", "sk_session_append", "sk_session_query",
     "sk_batch_step", "sk_session_query_shared_prefix", "sk_session_gather",
-    "sk_session_truncate", "sk_pool_set_profiling", "sk_pool_read_profile",
+    "sk_session_truncate", "sk_session_freeze", "sk_session_evict_oldest",
+    "sk_pool_set_profiling", "sk_pool_read_profile",
     "sk_pool_element_offset", "sk_pool_get_stats", "sk_pool_last_launch", "sk_strerror",
     "sk_last_hip_error", "sk_version",
 ]
@@ -100,6 +102,8 @@ def lib():
                                                  vp, vp, ctypes.c_int, vp, vp, vp]
     L.sk_session_gather.argtypes = [vp, i32, i64, i64, vp, vp, vp]
     L.sk_session_truncate.argtypes = [vp, i32, i64]
+    L.sk_session_freeze.argtypes = [vp, i32, i64]
+    L.sk_session_evict_oldest.argtypes = [vp, i32, i64, vp]
     L.sk_pool_set_profiling.argtypes = [vp, ctypes.c_int]
     L.sk_pool_read_profile.argtypes = [vp, P(sk_profile), P(ctypes.c_float), P(ctypes.c_float), i32]
     L.sk_pool_element_offset.restype = i64
@@ -237,6 +241,13 @@ class Pool:
 
     def sk_session_truncate(self, sid, new_length):
         _ck(lib().sk_session_truncate(self.h, sid, int(new_length)), "sk_session_truncate")
+
+    def sk_session_freeze(self, sid, n_frozen):
+        _ck(lib().sk_session_freeze(self.h, sid, int(n_frozen)), "sk_session_freeze")
+
+    def sk_session_evict_oldest(self, sid, n_tokens, stream=None):
+        _ck(lib().sk_session_evict_oldest(self.h, sid, int(n_tokens), _stream(stream) if self.kv_mem is not None else None),
+            "sk_session_evict_oldest")
 
     def sk_pool_set_profiling(self, enable):
         _ck(lib().sk_pool_set_profiling(self.h, int(bool(enable))), "sk_pool_set_profiling")

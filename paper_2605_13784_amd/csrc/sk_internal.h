@@ -53,7 +53,8 @@ struct sk_work {
     int32_t eph_blk[2];   // first staging block of each uncommitted segment
     int32_t eph_cnt[2];   // tokens in it (0 = absent)
     int32_t eph_pos0[2];  // absolute position of its first token
-    int32_t pad[2];
+    int32_t hole_lo;      // cached tokens [hole_lo, hole_hi) are evicted (Region-1 FIFO eviction): their
+    int32_t hole_hi;      // blocks are still streamed, the keys never attended to; empty when lo == hi
 };
 
 // One row tile of the cross-split combine.
@@ -95,6 +96,7 @@ struct sk_launch {
     // cached tokens cut into n_splits chunks of `chunk` tokens.
     int32_t tbl_off, n_tok, tok_per_tile, n_tiles, pos0, kv_len, chunk, n_splits;
     int32_t eph_blk[2], eph_cnt[2], eph_pos0[2];
+    int32_t hole_lo, hole_hi;    // evicted cached tokens of the session (regular mode)
     int32_t pad;
 };
 

@@ -72,6 +72,7 @@ __device__ __forceinline__ bool sk_decode_work(const sk_launch& P, int b, sk_wor
         w.kv_end = e < kv_vis ? e : kv_vis;
     }
     w.part = (P.n_splits == 1) ? -1 : (tile * P.n_splits + split) * Hkv + head;
+    w.hole_lo = P.hole_lo; w.hole_hi = P.hole_hi;
     for (int i = 0; i < 2; ++i) {
         w.eph_blk[i] = P.eph_blk[i]; w.eph_cnt[i] = eph_part ? P.eph_cnt[i] : 0; w.eph_pos0[i] = P.eph_pos0[i];
     }
@@ -88,6 +89,7 @@ struct sk_seg {
     int32_t v_off, B, log2B;
     int32_t begin, end;          // token indices; begin is a multiple of 16
     int32_t pos_shift;           // absolute position = token index + pos_shift
+    int32_t hole_lo, hole_n;     // tokens [hole_lo, hole_lo + hole_n) are evicted: streamed, never attended to
 };
 
 __device__ __forceinline__ sk_seg sk_make_seg(const sk_launch& P, const sk_work& w, int s)
@@ -98,11 +100,13 @@ __device__ __forceinline__ sk_seg sk_make_seg(const sk_launch& P, const sk_work&
         g.table = P.g.tables + w.tbl_off; g.blk_stride = P.g.blk_stride;
         g.v_off = P.g.v_off; g.B = P.g.B; g.log2B = P.g.log2B;
         g.begin = w.kv_begin; g.end = w.kv_end; g.pos_shift = 0;
+        g.hole_lo = w.hole_lo; g.hole_n = w.hole_hi - w.hole_lo;
     } else {
         g.base = P.g.eph + (int64_t)w.kv_head * P.g.eph_head_stride;
         g.table = P.g.eph_ident + (s == 1 ? w.eph_blk[0] : w.eph_blk[1]); g.blk_stride = P.g.eph_blk_stride;
         g.v_off = P.g.eph_v_off; g.B = 16; g.log2B = 4;
         g.begin = 0; g.end = (s == 1 ? w.eph_cnt[0] : w.eph_cnt[1]); g.pos_shift = (s == 1 ? w.eph_pos0[0] : w.eph_pos0[1]);
+        g.hole_lo = 0; g.hole_n = 0;
     }
     return g;
 }
@@ -412,7 +416,9 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
         // mask (only tiles that cross a limit), row maximum, P = exp2(s * scale - m), row sums
         auto step_softmax = [&](const int it) __attribute__((always_inline)) {
             const int pos_first = first_pos(it);
-            const bool need_mask = pos_first + TPW * SK_TILE - 1 > lim_wave_min;
+            // a tile is masked when it crosses a causal or end-of-segment limit, or touches evicted tokens
+            const bool need_mask = pos_first + TPW * SK_TILE - 1 > lim_wave_min ||
+                                   (pos_first < g.hole_lo + g.hole_n && pos_first + TPW * SK_TILE > g.hole_lo);
             // the maximum is taken on the raw scores; the softmax scale is applied inside the
             // exponent below (one FMA per score)
             float mt_ = SK_NEG_INF;
@@ -422,7 +428,8 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int pos = pos_first + t * SK_TILE + 16 * (v >> 3) + 8 * kg + (v & 7);
-                        const float x = (pos <= lim_row) ? sacc[t][v] : SK_NEG_INF;
+                        const bool vis = pos <= lim_row && (unsigned)(pos - g.hole_lo) >= (unsigned)g.hole_n;
+                        const float x = vis ? sacc[t][v] : SK_NEG_INF;
                         sacc[t][v] = x;
                         mt_ = fmaxf(mt_, x);
                     }
@@ -856,7 +863,7 @@ __global__ __launch_bounds__(256) void sk_attn_simple(const sk_launch P)
                 float acc = 0.f;
                 for (int t = 0; t < d; ++t) acc = fmaf(Qs[r][t], Ks[tt][t], acc);
                 float x = acc * c_scale;
-                x = (t0 + tt + g.pos_shift <= lim) ? x : SK_NEG_INF;
+                x = (t0 + tt + g.pos_shift <= lim && (unsigned)(t0 + tt - g.hole_lo) >= (unsigned)g.hole_n) ? x : SK_NEG_INF;
                 sc[j] = x;
                 mt_ = fmaxf(mt_, x);
             }

@@ -25,10 +25,17 @@ constexpr int kDefaultTargetWgs = 512;
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int ilog2_exact(int64_t x) { int l = 0; while ((int64_t(1) << l) < x) ++l; return ((int64_t(1) << l) == x) ? l : -1; }
 
+// A session's tokens live at *storage indices* 0 .. len-1; block i of `blocks` holds storage
+// indices i*B .. i*B+B-1.  Storage indices [frozen, win) are evicted (Region-1 FIFO eviction behind
+// a frozen Region 0): what the session holds is [0, frozen) followed by [win, len).  Whole blocks
+// inside the hole are returned to the pool and the storage indices behind them shifted down, so
+// the hole always spans less than two blocks; what is left of it is masked in the kernels.
 struct Session {
     bool live = false;
     int64_t len = 0;
+    int64_t frozen = 0, win = 0;
     std::vector<int32_t> blocks;
+    int64_t retained() const { return frozen + (len - win); }
 };
 
 struct Layout {
@@ -248,6 +255,7 @@ int run_regular(sk_pool* p, int32_t id, const void* q, int64_t n_tok, int32_t po
     L.chunk = (int32_t)chunk;
     L.n_splits = (int32_t)parts;
     L.eph_blk[0] = 0; L.eph_cnt[0] = eph_cnt; L.eph_pos0[0] = eph_pos0;
+    L.hole_lo = (int32_t)p->sessions[id].frozen; L.hole_hi = (int32_t)p->sessions[id].win;
 #ifdef SK_EXPERIMENT
     if (const char* x = getenv("SK_EXPERIMENT")) L.pad = atoi(x);
     if (const char* x = getenv("SK_DEBUG_PTR")) L.work = (const sk_work*)strtoull(x, nullptr, 0);
@@ -340,6 +348,7 @@ struct TileReq {            // one tile of query rows and the keys it may see
     int32_t pos0;           // absolute position of its first token, or SK_NO_CAUSAL
     int32_t kv_vis;         // cached tokens visible to the tile (positions 0 .. kv_vis-1)
     int32_t eph_blk[2], eph_cnt[2], eph_pos0[2];
+    int32_t hole_lo, hole_hi;   // evicted cached tokens of the session
 };
 struct ListGroup {          // tiles that share a kernel variant and the q/out/lse arrays
     Variant v = {SK_KV_SIMPLE, 16, 1};
@@ -414,6 +423,7 @@ int run_list(sk_pool* p, ScatterBatch* sb, int n_sb, ListGroup* groups, int n_gr
                             w.kv_begin = int32_t(part * chunk);
                             w.kv_end = int32_t(std::min<int64_t>(t.kv_vis, (part + 1) * chunk));
                             w.part = np > 1 ? slot0[i - i0] + part * Hkv + h : -1;
+                            w.hole_lo = t.hole_lo; w.hole_hi = t.hole_hi;
                             if (part == np - 1)
                                 for (int e = 0; e < 2; ++e) { w.eph_blk[e] = t.eph_blk[e]; w.eph_cnt[e] = t.eph_cnt[e]; w.eph_pos0[e] = t.eph_pos0[e]; }
                             work[gi].push_back(w);
@@ -614,7 +624,7 @@ int sk_session_create(sk_pool* p, int32_t* out_id)
     int32_t id = p->free_ids.back();
     p->free_ids.pop_back();
     Session& s = p->sessions[id];
-    s.live = true; s.len = 0; s.blocks.clear();
+    s.live = true; s.len = 0; s.frozen = 0; s.win = 0; s.blocks.clear();
     *out_id = id;
     return SK_OK;
 }
@@ -625,7 +635,7 @@ int sk_session_destroy(sk_pool* p, int32_t id)
     if (!s) return p ? SK_E_BADSESSION : SK_E_INVAL;
     for (int32_t b : s->blocks) p->free_blocks.push_back(b);
     p->blocks_in_use -= (int64_t)s->blocks.size();
-    s->blocks.clear(); s->len = 0; s->live = false;
+    s->blocks.clear(); s->len = 0; s->frozen = 0; s->win = 0; s->live = false;
     p->free_ids.push_back(id);
     return SK_OK;
 }
@@ -635,7 +645,7 @@ int sk_session_length(const sk_pool* p, int32_t id, int64_t* out)
     const Session* s = get_session(p, id);
     if (!p || !out) return SK_E_INVAL;
     if (!s) return SK_E_BADSESSION;
-    *out = s->len;
+    *out = s->retained();
     return SK_OK;
 }
 
@@ -698,7 +708,7 @@ int sk_session_query(sk_pool* p, int32_t id, const void* q, const void* k, const
     int rc = check_out_dtype(p, out_dtype);
     if (rc) return rc;
     if (nq > p->L.max_batch_tokens) return SK_E_WORKSPACE;
-    if (!k && s->len == 0) return SK_E_EMPTY;
+    if (!k && s->retained() == 0) return SK_E_EMPTY;
     Variant vv;
     if (!pick_variant(p, nq, vv)) return SK_E_SHAPE;
     hipStream_t st = (hipStream_t)hip_stream;
@@ -737,7 +747,7 @@ int sk_batch_step(sk_pool* p, int32_t n_items, const int32_t* session_id, const 
             if (s->len + T > p->L.max_session_tokens) return SK_E_NOMEM;
             need_blocks += blocks_needed(p, s->len, T);
         }
-        if (op[i] == SK_OP_QUERY_A && s->len == 0) return SK_E_EMPTY;
+        if (op[i] == SK_OP_QUERY_A && s->retained() == 0) return SK_E_EMPTY;
         if (op[i] != SK_OP_QUERY_A) any_kv = true;
     }
     const int64_t total = cu_tokens[n_items];
@@ -767,6 +777,7 @@ int sk_batch_step(sk_pool* p, int32_t n_items, const int32_t* session_id, const 
         const int32_t tbl_off = int32_t(int64_t(id) * p->L.max_blocks_per_session);
         TileReq base = {};
         base.tbl_off = tbl_off;
+        base.hole_lo = (int32_t)s->frozen; base.hole_hi = (int32_t)s->win;
         if (op[i] == SK_OP_APPEND) {
             const int64_t first_new = (int64_t)s->blocks.size();
             take_blocks(p, s, blocks_needed(p, n, T));
@@ -832,6 +843,7 @@ int sk_session_query_shared_prefix(sk_pool* p, int32_t id, const void* qp, const
         build_scatter(p, nullptr, id, 0, 0, P, 0, true, 0, sb[0].items);
         TileReq base = {};
         base.tbl_off = tbl_off; base.pos0 = (int32_t)n; base.kv_vis = (int32_t)n;
+        base.hole_lo = (int32_t)s->frozen; base.hole_hi = (int32_t)s->win;
         base.eph_blk[0] = 0; base.eph_cnt[0] = P; base.eph_pos0[0] = (int32_t)n;
         pick_variant(p, P, groups[0].v);
         groups[0].q = qp; groups[0].out = out_prefix; groups[0].lse = lse_prefix;
@@ -846,6 +858,7 @@ int sk_session_query_shared_prefix(sk_pool* p, int32_t id, const void* qp, const
             build_scatter(p, nullptr, id, 0, j * Sfx, Sfx, 0, true, blk, sb[1].items);
             TileReq base = {};
             base.tbl_off = tbl_off; base.pos0 = int32_t(n + P); base.kv_vis = (int32_t)n;
+            base.hole_lo = (int32_t)s->frozen; base.hole_hi = (int32_t)s->win;
             base.eph_blk[0] = 0; base.eph_cnt[0] = P; base.eph_pos0[0] = (int32_t)n;
             base.eph_blk[1] = (int32_t)blk; base.eph_cnt[1] = Sfx; base.eph_pos0[1] = int32_t(n + P);
             add_tiles(groups[1], base, j * Sfx, Sfx);
@@ -860,11 +873,23 @@ int sk_session_gather(const sk_pool* p, int32_t id, int64_t first, int64_t count
     const Session* s = get_session(p, id);
     if (!s) return SK_E_BADSESSION;
     if (!p->device) return SK_E_NODEVICE;
-    if (first < 0 || count < 0 || first + count > s->len) return SK_E_INVAL;
+    if (first < 0 || count < 0 || first + count > s->retained()) return SK_E_INVAL;
     if (count == 0) return SK_OK;
     if (!k_out || !v_out || !aligned16(k_out) || !aligned16(v_out)) return SK_E_INVAL;
-    int e = sk_launch_gather(p->geom, int32_t(int64_t(id) * p->L.max_blocks_per_session), first, count, k_out, v_out, hip_stream);
-    if (e) { g_last_hip = e; return SK_E_HIP; }
+    // retained tokens [first, first+count) = a piece of [0, frozen) followed by a piece of [win, len)
+    const int32_t tbl_off = int32_t(int64_t(id) * p->L.max_blocks_per_session);
+    const int64_t row_bytes = int64_t(p->d.n_kv_heads) * p->d.head_dim * p->L.elem;
+    const int64_t n_a = std::max<int64_t>(0, std::min(first + count, s->frozen) - first);
+    if (n_a > 0) {
+        int e = sk_launch_gather(p->geom, tbl_off, first, n_a, k_out, v_out, hip_stream);
+        if (e) { g_last_hip = e; return SK_E_HIP; }
+    }
+    if (count > n_a) {
+        const int64_t first_b = std::max(first, s->frozen) - s->frozen + s->win;
+        int e = sk_launch_gather(p->geom, tbl_off, first_b, count - n_a, (unsigned char*)k_out + n_a * row_bytes,
+                                 (unsigned char*)v_out + n_a * row_bytes, hip_stream);
+        if (e) { g_last_hip = e; return SK_E_HIP; }
+    }
     return SK_OK;
 }
 
@@ -873,15 +898,61 @@ int sk_session_truncate(sk_pool* p, int32_t id, int64_t new_length)
     if (!p) return SK_E_INVAL;
     Session* s = get_session(p, id);
     if (!s) return SK_E_BADSESSION;
-    if (new_length < 0 || new_length > s->len) return SK_E_INVAL;
+    if (new_length < 0 || new_length > s->retained()) return SK_E_INVAL;
+    if (new_length <= s->frozen) { s->frozen = new_length; s->win = new_length; s->len = new_length; }
+    else s->len = s->win + (new_length - s->frozen);
     const int64_t B = p->d.block_tokens;
-    const size_t keep = size_t((new_length + B - 1) / B);
+    const size_t keep = size_t((s->len + B - 1) / B);
     while (s->blocks.size() > keep) {
         p->free_blocks.push_back(s->blocks.back());
         s->blocks.pop_back();
         p->blocks_in_use--;
     }
-    s->len = new_length;
+    return SK_OK;
+}
+
+int sk_session_freeze(sk_pool* p, int32_t id, int64_t n_frozen)
+{
+    if (!p) return SK_E_INVAL;
+    Session* s = get_session(p, id);
+    if (!s) return SK_E_BADSESSION;
+    if (s->win != s->frozen) return SK_E_INVAL;           // tokens behind the frozen region were already evicted
+    if (n_frozen < s->frozen || n_frozen > s->len) return SK_E_INVAL;
+    s->frozen = n_frozen; s->win = n_frozen;
+    return SK_OK;
+}
+
+int sk_session_evict_oldest(sk_pool* p, int32_t id, int64_t n_tokens, void* hip_stream)
+{
+    if (!p) return SK_E_INVAL;
+    Session* s = get_session(p, id);
+    if (!s) return SK_E_BADSESSION;
+    if (n_tokens < 0 || n_tokens > s->len - s->win) return SK_E_INVAL;
+    if (n_tokens == 0) return SK_OK;
+    s->win += n_tokens;
+    p->stats.tokens_evicted += n_tokens;
+    // blocks that lie entirely inside the hole go back to the pool; storage indices behind them move down
+    const int64_t B = p->d.block_tokens;
+    const int64_t b0 = (s->frozen + B - 1) / B, b1 = s->win / B;
+    if (b1 <= b0) return SK_OK;
+    const int64_t k = b1 - b0;
+    for (int64_t b = b0; b < b1; ++b) p->free_blocks.push_back(s->blocks[(size_t)b]);
+    s->blocks.erase(s->blocks.begin() + b0, s->blocks.begin() + b1);
+    p->blocks_in_use -= k;
+    s->win -= k * B; s->len -= k * B;
+    if (!p->device || s->blocks.size() == (size_t)b0) return SK_OK;
+    // rewrite the moved tail of the session's device block table (ordered on the caller's stream)
+    int slot; unsigned char* host;
+    int rc = ring_acquire(p, &slot, &host);
+    if (rc) return rc;
+    const size_t bytes = (s->blocks.size() - (size_t)b0) * sizeof(int32_t);
+    if (bytes > kMetaBytes) return SK_E_WORKSPACE;         // more than a million blocks behind the hole
+    memcpy(host, s->blocks.data() + b0, bytes);
+    int32_t* dev_tbl = (int32_t*)((unsigned char*)p->d.workspace + p->L.off_tables) + int64_t(id) * p->L.max_blocks_per_session + b0;
+    hipStream_t st = (hipStream_t)hip_stream;
+    SK_HIP(hipMemcpyAsync(dev_tbl, host, bytes, hipMemcpyHostToDevice, st));
+    SK_HIP(hipEventRecord(p->ring_ev[slot], st));
+    p->ring_used[slot] = true;
     return SK_OK;
 }
 

@@ -99,3 +99,11 @@ class Pair:
         assert self.pool.sk_session_length(sid) == Kc.shape[0]
         np.testing.assert_array_equal(synth.to_raw(k.cpu()), Kc)
         np.testing.assert_array_equal(synth.to_raw(v.cpu()), Vc)
+
+    def freeze(self, sid, n_frozen):
+        self.pool.sk_session_freeze(sid, n_frozen)
+        self.oracles[sid].freeze(n_frozen)
+
+    def evict(self, sid, n_tokens):
+        self.pool.sk_session_evict_oldest(sid, n_tokens)
+        self.oracles[sid].evict_oldest(n_tokens)

@@ -1,0 +1,108 @@
+"""GPU parity of Region-1 FIFO eviction behind a frozen Region 0 (Sec. 3.3; Alg. 1 evict_oldest):
+after every eviction the appends, both kinds of query and the batched calls equal the oracle's
+attention over [frozen tokens ; retained tokens], and the retained K/V read back bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2605_13784_amd as sk
+from workloads import synth
+from gpu_common import Pair, compare, dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("shape,block_tokens,n_frozen", [
+    (synth.CFG2, 16, 100),        # frozen end inside a block, hole inside blocks
+    (synth.CFG2, 16, 64),         # frozen end on a block boundary
+    (synth.CFG2, 64, 37),         # blocks of 64: the hole spans whole key tiles of the kernel
+    (synth.CFG2, 256, 0),         # no frozen region, large blocks: a hole of up to 255 tokens in front
+    (synth.CFG1, 16, 21),         # fp32 kernel
+])
+def test_sliding_window_stream(shape, block_tokens, n_frozen):
+    """A stream that keeps a window: append, evict what exceeds the capacity, query; several rounds,
+    with eviction amounts that leave the hole at every alignment."""
+    gen = synth.generator(2, stream=30 + block_tokens + n_frozen)
+    cap = 900
+    pr = Pair(shape, block_tokens=block_tokens, n_blocks=4096 // block_tokens + 8, kv_fill=0xFF, max_batch_tokens=1024)
+    sid = pr.create()
+    if n_frozen:
+        q, k, v = synth.draw_qkv(gen, n_frozen, shape)
+        pr.append(sid, q, k, v, name="frozen prefix")
+        pr.freeze(sid, n_frozen)
+    free0 = None
+    for step, L in enumerate([300, 333, 257, 64, 1, 15, 290, 130, 256]):
+        q, k, v = synth.draw_qkv(gen, L, shape)
+        over = pr.pool.sk_session_length(sid) + L - cap
+        if over > 0:
+            pr.evict(sid, over)                       # Alg. 1: evict_oldest before the append
+        pr.append(sid, q, k, v, name="append %d (L=%d)" % (step, L))
+        assert pr.pool.sk_session_length(sid) == pr.oracles[sid].length <= cap
+        pr.check_cache(sid)
+        qq, kq, vq = synth.draw_qkv(gen, 32 if step % 2 else 5, shape)
+        pr.query(sid, qq, name="query A after step %d" % step)
+        pr.query(sid, qq, kq, vq, n_splits=3, name="query B after step %d" % step)
+    # blocks in use never exceed what capacity + frozen + two partly evicted blocks need
+    used = len(pr.pool.sk_session_block_table(sid))
+    assert used <= (cap + block_tokens - 1) // block_tokens + 2
+    # evict the whole window: only the frozen region is attended to
+    pr.evict(sid, pr.pool.sk_session_length(sid) - n_frozen)
+    assert pr.pool.sk_session_length(sid) == n_frozen
+    if n_frozen:
+        qq, kq, vq = synth.draw_qkv(gen, 9, shape)
+        pr.query(sid, qq, name="query A, window empty")
+        pr.query(sid, qq, kq, vq, name="query B, window empty")
+        pr.check_cache(sid)
+    else:
+        with pytest.raises(sk.SkError) as e:
+            pr.pool.sk_session_query(sid, dev(synth.draw(gen, (4, shape.n_q_heads, shape.head_dim), shape.dtype)))
+        assert e.value.status == sk.SK_E_EMPTY
+    q, k, v = synth.draw_qkv(gen, 70, shape)
+    pr.append(sid, q, k, v, name="append after emptying the window")
+    pr.check_cache(sid)
+
+
+def test_eviction_in_batched_calls_and_truncate():
+    """Sessions with evicted tokens inside a batch step and a question batch; truncate counts
+    retained tokens."""
+    shape = synth.CFG4
+    gen = synth.generator(4, stream=31)
+    pool = sk.Pool(shape.dtype, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, 16, 400, max_sessions=3,
+                   max_batch_tokens=2048, kv_fill=0xFF)
+    ref = oracle.OraclePool(shape.dtype, shape.n_q_heads, shape.n_kv_heads, shape.head_dim)
+    sids = [pool.sk_session_create() for _ in range(3)]
+    for _ in sids:
+        ref.create()
+    plan = [(700, 50, 123), (1500, 0, 1000), (300, 300, 0)]      # (tokens, frozen, evicted)
+    for sid, (n, nf, ne) in zip(sids, plan):
+        q, k, v = synth.draw_qkv(gen, n, shape)
+        pool.sk_session_append(sid, None, dev(k), dev(v))
+        o = ref.sessions[sid]
+        o.K, o.V = synth.to_raw(k), synth.to_raw(v)
+        pool.sk_session_freeze(sid, nf); o.freeze(nf)
+        pool.sk_session_evict_oldest(sid, ne); o.evict_oldest(ne)
+    ops = [sk.SK_OP_APPEND, sk.SK_OP_QUERY_B, sk.SK_OP_QUERY_A]
+    cu = np.array([0, 200, 240, 300], dtype=np.int32)
+    q, k, v = synth.draw_qkv(gen, 300, shape)
+    out, lse = pool.sk_batch_step(sids, ops, cu, dev(q), dev(k), dev(v))
+    ro, rl = ref.batch_step(sids, ops, cu, synth.to_raw(q), synth.to_raw(k), synth.to_raw(v))
+    compare("batch step", out, lse, ro, rl, shape.dtype)
+    for sid in sids:
+        kk, vv = pool.sk_session_gather(sid)
+        torch.cuda.synchronize()
+        K, V = ref.sessions[sid].cache()
+        np.testing.assert_array_equal(synth.to_raw(kk.cpu()), K)
+        np.testing.assert_array_equal(synth.to_raw(vv.cpu()), V)
+    # truncate into the window, then into the frozen region, and keep going
+    a = sids[0]
+    pool.sk_session_truncate(a, 400); ref.sessions[a].truncate(400)
+    qq, kq, vq = synth.draw_qkv(gen, 16, shape)
+    out, lse = pool.sk_session_query(a, dev(qq), dev(kq), dev(vq))
+    ro, rl = ref.sessions[a].query(synth.to_raw(qq), synth.to_raw(kq), synth.to_raw(vq))
+    compare("query after truncate into the window", out, lse, ro, rl, shape.dtype)
+    pool.sk_session_truncate(a, 30); ref.sessions[a].truncate(30)
+    out, lse = pool.sk_session_query(a, dev(qq))
+    ro, rl = ref.sessions[a].query(synth.to_raw(qq))
+    compare("query after truncate into the frozen region", out, lse, ro, rl, shape.dtype)
+    assert pool.sk_session_length(a) == 30

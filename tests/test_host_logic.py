@@ -163,3 +163,37 @@ def test_truncate_returns_whole_blocks_only():
         p.sk_session_truncate(a, 1)         # cannot grow
     p.reserve(a, 16)
     assert p.sk_session_block_table(a) == [3]          # freed blocks queue behind the untouched ones
+
+
+def test_eviction_metadata():
+    """Region-1 FIFO eviction behind a frozen prefix: lengths count retained tokens, blocks that
+    hold only evicted tokens return to the pool at once, the table is compacted, appends continue
+    behind the window, truncate and freeze respect the frozen region."""
+    p = meta_pool(n_blocks=16, block_tokens=16)
+    a = p.sk_session_create()
+    p.reserve(a, 100)                                   # blocks 0..6
+    p.sk_session_freeze(a, 20)                          # frozen: block 0 and 4 tokens of block 1
+    assert p.sk_session_length(a) == 100
+    p.sk_session_evict_oldest(a, 10)                    # storage [20,30): inside block 1, nothing freed
+    assert p.sk_session_length(a) == 90 and p.sk_session_block_table(a) == [0, 1, 2, 3, 4, 5, 6]
+    p.sk_session_evict_oldest(a, 30)                    # storage [20,60): blocks 2 and 3... block 2 = [32,48) goes, block 3 = [48,64) stays
+    assert p.sk_session_length(a) == 60 and p.sk_session_block_table(a) == [0, 1, 3, 4, 5, 6]
+    assert p.sk_pool_blocks_free() == 10
+    p.sk_session_evict_oldest(a, 4)                     # up to the end of block 3: it goes too
+    assert p.sk_session_block_table(a) == [0, 1, 4, 5, 6] and p.sk_session_length(a) == 56
+    with pytest.raises(sk.SkError) as e:
+        p.sk_session_evict_oldest(a, 37)                # only 36 tokens left behind the frozen region
+    assert e.value.status == sk.SK_E_INVAL and p.sk_session_length(a) == 56
+    with pytest.raises(sk.SkError):
+        p.sk_session_freeze(a, 30)                      # not after an eviction
+    p.reserve(a, 20)                                    # 4 tokens fill block 6, one new block
+    assert p.sk_session_length(a) == 76 and len(p.sk_session_block_table(a)) == 6
+    p.sk_session_truncate(a, 25)                        # 20 frozen + 5 of the window
+    assert p.sk_session_length(a) == 25
+    p.sk_session_truncate(a, 7)                         # into the frozen region
+    assert p.sk_session_length(a) == 7 and p.sk_session_block_table(a) == [0]
+    p.sk_session_evict_oldest(a, 0)
+    with pytest.raises(sk.SkError):
+        p.sk_session_evict_oldest(a, 1)                 # nothing behind the frozen region
+    st = p.sk_pool_get_stats()
+    assert st["tokens_evicted"] == 44

@@ -390,3 +390,48 @@ def test_bf16_inputs_are_widened_exactly():
     ob, lb = b.query(f(q16))
     np.testing.assert_array_equal(oa, ob)
     np.testing.assert_array_equal(la, lb)
+
+
+def test_eviction_attends_over_frozen_prefix_and_retained_window_only():
+    """Region 0 frozen, Region 1 FIFO-evicted (Sec. 3.3; Alg. 1 evict_oldest): after evicting, every
+    row equals a pure-Python softmax over [frozen tokens ; retained tokens] in their original order;
+    a needle in the frozen region is still retrieved, one in the evicted range is lost (the paper's
+    "attention over that data is lost"), evicting nothing changes nothing."""
+    Hq, Hkv, d, n, nf, ne = 2, 1, 4, 20, 5, 7
+    rng = np.random.default_rng(11)
+    K, V = _rand(rng, (n, Hkv, d), "f32"), _rand(rng, (n, Hkv, d), "f32")
+    q = _rand(rng, (2, Hq, d), "f32")
+    s = OracleSession("f32", Hq, Hkv, d)
+    s.append(np.zeros((n, Hq, d), np.float32), K, V)
+    before = s.query(q)
+    s.freeze(nf)
+    s.evict_oldest(0)
+    np.testing.assert_array_equal(s.query(q)[0], before[0])
+    s.evict_oldest(ne)
+    assert s.length == n - ne
+    keep = list(range(nf)) + list(range(nf + ne, n))
+    np.testing.assert_array_equal(s.cache()[0], K[keep])
+    o, l = s.query(q)
+    for i in range(2):
+        for h in range(Hq):
+            ro, rl = _brute_row(q[i, h].tolist(), [K[t, 0].tolist() for t in keep], [V[t, 0].tolist() for t in keep], 0.5)
+            np.testing.assert_allclose(o[i, h], ro, rtol=1e-12, atol=1e-13)
+            assert abs(l[i, h] - rl) < 1e-12
+    # appended tokens go behind the retained window and see all of it
+    k2, v2, q2 = _rand(rng, (3, Hkv, d), "f32"), _rand(rng, (3, Hkv, d), "f32"), _rand(rng, (3, Hq, d), "f32")
+    o2, _ = s.append(q2, k2, v2)
+    ro, _ = _brute_row(q2[0, 1].tolist(), [K[t, 0].tolist() for t in keep] + [k2[0, 0].tolist()],
+                       [V[t, 0].tolist() for t in keep] + [v2[0, 0].tolist()], 0.5)
+    np.testing.assert_allclose(o2[0, 1], ro, rtol=1e-12, atol=1e-13)
+    # needles: frozen survives, evicted is lost
+    for pos, survives in ((2, True), (8, False)):
+        t = OracleSession("f32", Hq, Hkv, d)
+        K2 = K.copy(); K2[pos, 0] = 300.0 * q[0, 0] / np.linalg.norm(q[0, 0])
+        t.append(np.zeros((n, Hq, d), np.float32), K2, V)
+        t.freeze(nf); t.evict_oldest(ne)
+        got = t.query(q)[0][0, 0]
+        assert np.allclose(got, V[pos, 0].astype(np.float64), atol=1e-9) == survives
+    with pytest.raises(ValueError):
+        s.evict_oldest(s.length - nf + 1)              # more than Region 1 holds
+    with pytest.raises(ValueError):
+        s.freeze(nf - 1)                               # the frozen region only grows
