@@ -145,6 +145,7 @@ def main():
         extras["cfg5_question_batch_64k"] = question_batch(sk)
         extras["cfg4_multi_tenant_step"] = multi_tenant(sk)
         extras["sliding_window_32k"] = sliding_window(sk)
+        extras["fork_cost"] = fork_cost(sk)
         res["extras"] = extras
     if not args.no_cpu_baseline:
         rows = args.cpu_rows or ((L + nq) * shape.n_q_heads if n <= 32768 else 4096)
@@ -286,6 +287,30 @@ def sliding_window(sk, cap=32768, n_frozen=500, L=256, nq=32, n_sessions=9, step
     return {"retained_tokens": int(length), "frozen_tokens": n_frozen, "evict_append_query_ms_per_step": wall * 1e3 / steps,
             "tokens_per_s": (L + nq) * steps / wall, "evict_call_host_us_incl_wait_for_upload_slot": evict_host_s * 1e6 / steps,
             "blocks_per_session": blocks, "block_table_bytes_copied_per_evict": (blocks - (n_frozen + B - 1) // B) * 4}
+
+
+def fork_cost(sk, n=32768 + 7, reps=20):
+    """sk_session_fork of a prefix of a 32K-token session: host call + the device work it enqueues
+    (block-table upload, copy of one partly filled block), synchronised; by prefix length."""
+    shape = synth.CFG2
+    B = 16
+    pool = sk.Pool(shape.dtype, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, B, n // B + 64,
+                   max_sessions=2, max_batch_tokens=1024)
+    gen = synth.generator(2, stream=41)
+    (src,) = build_sessions(pool, shape, n, 1024, 1, gen)
+    res = {}
+    for n_prefix in (1000, 8200, n):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            f = pool.sk_session_fork(src, n_prefix)
+            torch.cuda.synchronize()
+            pool.sk_session_destroy(f)
+        res["prefix_%d_us" % n_prefix] = (time.perf_counter() - t0) * 1e6 / reps
+    res["bytes_per_fork_at_32775"] = {"block_table": 4 * ((n + B - 1) // B), "block_copy": B * shape.kv_bytes_per_token,
+                                      "kv_shared_not_copied": (n // B) * B * shape.kv_bytes_per_token}
+    pool.close()
+    return res
 
 
 def question_batch(sk, n=65536, L=256, P=16, NQ=64, Sfx=8, cycles=8):

@@ -204,15 +204,30 @@ int sk_session_truncate(sk_pool* pool, int32_t id, int64_t new_length);
 int sk_session_freeze(sk_pool* pool, int32_t id, int64_t n_frozen);
 int sk_session_evict_oldest(sk_pool* pool, int32_t id, int64_t n_tokens, void* hip_stream);
 
+/*
+ * FORK (Sec. 3.7 prefix-aware grouped prefill: followers alias the leader's state; Sec. 3.10
+ * metadata-only sequence aliasing).  Creates a session whose cache is the first n_prefix retained
+ * tokens of session src (including src's frozen region and evicted range as far as the prefix
+ * reaches).  The blocks of the prefix are shared, not copied (per-block reference counts; a
+ * block returns to the free list when its last holder drops it); only when the prefix ends
+ * inside a block does the new session get a copy of that one block, into which its own appends
+ * then go.  Cost: n_prefix / block_tokens table entries and at most one block of K/V, whatever the
+ * prefix length.  Afterwards the two sessions are independent: appends, evictions, truncations
+ * and destruction of one never change what the other reads.
+ * The device work (table upload, block copy) is ordered on hip_stream, which must be the stream
+ * of src's earlier calls.  SK_E_NOMEM when no session id or (if needed) no block is free.
+ */
+int sk_session_fork(sk_pool* pool, int32_t src, int64_t n_prefix, int32_t* out_id, void* hip_stream);
+
 /* Byte offset inside kv_mem of element (block, kv_head, is_v, slot, dim), so a harness can
  * address the pool without knowing the layout.  Negative on bad arguments. */
 int64_t sk_pool_element_offset(const sk_pool* pool, int64_t block, int32_t kv_head, int32_t is_v,
                                int32_t slot, int32_t dim);
 
 /* Counters since creation: tokens appended, query tokens, kernel launches, cached-token
- * bytes the attention kernels were asked to stream, tokens evicted. */
+ * bytes the attention kernels were asked to stream, tokens evicted, sessions forked. */
 typedef struct sk_pool_stats {
-    int64_t tokens_appended, tokens_queried, launches, kv_bytes_streamed, tokens_evicted;
+    int64_t tokens_appended, tokens_queried, launches, kv_bytes_streamed, tokens_evicted, forks;
 } sk_pool_stats;
 int sk_pool_get_stats(const sk_pool* pool, sk_pool_stats* out);
 

@@ -121,6 +121,16 @@ class OracleSession:
         self.K = np.concatenate([self.K[:a], self.K[b:]], axis=0)
         self.V = np.concatenate([self.V[:a], self.V[b:]], axis=0)
 
+    def fork(self, n_prefix):
+        """A new session holding the first n_prefix tokens of this one (Sec. 3.7 followers aliasing the
+        leader's state; Sec. 3.10 sequence aliasing): by value here, the two never interact."""
+        if not (0 <= n_prefix <= self.length):
+            raise ValueError("n_prefix")
+        t = OracleSession(self.dtype, self.Hq, self.Hkv, self.d, self.scale)
+        t.K, t.V = self.K[:n_prefix].copy(), self.V[:n_prefix].copy()
+        t.n_frozen = min(self.n_frozen, int(n_prefix))
+        return t
+
     @property
     def length(self):
         return self.K.shape[0]

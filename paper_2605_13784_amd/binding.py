@@ -43,7 +43,7 @@ class sk_pool_desc(ctypes.Structure):
 class sk_pool_stats(ctypes.Structure):
     _fields_ = [("tokens_appended", ctypes.c_int64), ("tokens_queried", ctypes.c_int64),
                 ("launches", ctypes.c_int64), ("kv_bytes_streamed", ctypes.c_int64),
-                ("tokens_evicted", ctypes.c_int64)]
+                ("tokens_evicted", ctypes.c_int64), ("forks", ctypes.c_int64)]
 
 
 class sk_launch_info(ctypes.Structure):
@@ -60,7 +60,7 @@ EXPORTS = [
     "sk_pool_blocks_free", "sk_pool_set_alloc_order", "sk_session_create", "sk_session_destroy",
     "sk_session_length", "sk_session_block_table", "sk_session_append", "sk_session_query",
     "sk_batch_step", "sk_session_query_shared_prefix", "sk_session_gather",
-    "sk_session_truncate", "sk_session_freeze", "sk_session_evict_oldest",
+    "sk_session_truncate", "sk_session_freeze", "sk_session_evict_oldest", "sk_session_fork",
     "sk_pool_set_profiling", "sk_pool_read_profile",
     "sk_pool_element_offset", "sk_pool_get_stats", "sk_pool_last_launch", "sk_strerror",
     "sk_last_hip_error", "sk_version",
@@ -104,6 +104,7 @@ def lib():
     L.sk_session_truncate.argtypes = [vp, i32, i64]
     L.sk_session_freeze.argtypes = [vp, i32, i64]
     L.sk_session_evict_oldest.argtypes = [vp, i32, i64, vp]
+    L.sk_session_fork.argtypes = [vp, i32, i64, P(i32), vp]
     L.sk_pool_set_profiling.argtypes = [vp, ctypes.c_int]
     L.sk_pool_read_profile.argtypes = [vp, P(sk_profile), P(ctypes.c_float), P(ctypes.c_float), i32]
     L.sk_pool_element_offset.restype = i64
@@ -244,6 +245,12 @@ class Pool:
 
     def sk_session_freeze(self, sid, n_frozen):
         _ck(lib().sk_session_freeze(self.h, sid, int(n_frozen)), "sk_session_freeze")
+
+    def sk_session_fork(self, src, n_prefix, stream=None):
+        out = ctypes.c_int32()
+        _ck(lib().sk_session_fork(self.h, src, int(n_prefix), ctypes.byref(out),
+                                  _stream(stream) if self.kv_mem is not None else None), "sk_session_fork")
+        return out.value
 
     def sk_session_evict_oldest(self, sid, n_tokens, stream=None):
         _ck(lib().sk_session_evict_oldest(self.h, sid, int(n_tokens), _stream(stream) if self.kv_mem is not None else None),

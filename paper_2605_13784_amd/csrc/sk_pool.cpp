@@ -102,6 +102,7 @@ struct sk_pool {
     std::vector<Session> sessions;
     std::vector<int32_t> free_ids;
     int64_t blocks_in_use = 0;
+    std::vector<int32_t> refcnt;         // sessions holding each block (forks share the blocks of a prefix)
     // pinned staging ring for uploaded lists
     unsigned char* ring = nullptr;
     hipEvent_t ring_ev[kRingSlots] = {};
@@ -330,9 +331,16 @@ void take_blocks(sk_pool* p, Session* s, int64_t need)
 {
     for (int64_t i = 0; i < need; ++i) {
         s->blocks.push_back(p->free_blocks.front());
+        p->refcnt[(size_t)p->free_blocks.front()] = 1;
         p->free_blocks.pop_front();
     }
     p->blocks_in_use += need;
+}
+
+// One session lets go of a block; the last holder returns it to the free list.
+void release_block(sk_pool* p, int32_t b)
+{
+    if (--p->refcnt[(size_t)b] == 0) { p->free_blocks.push_back(b); p->blocks_in_use--; }
 }
 
 int check_out_dtype(const sk_pool* p, int out_dtype)
@@ -550,6 +558,7 @@ int sk_pool_create(const sk_pool_desc* desc, sk_pool** out)
     p->L = L;
     p->device = !meta_only;
     for (int64_t i = 0; i < desc->n_blocks; ++i) p->free_blocks.push_back((int32_t)i);
+    p->refcnt.assign((size_t)desc->n_blocks, 0);
     p->sessions.resize(desc->max_sessions);
     for (int32_t i = desc->max_sessions - 1; i >= 0; --i) p->free_ids.push_back(i);
     const float scale = desc->softmax_scale != 0.f ? desc->softmax_scale : 1.0f / std::sqrt((float)desc->head_dim);
@@ -633,8 +642,7 @@ int sk_session_destroy(sk_pool* p, int32_t id)
 {
     Session* s = get_session(p, id);
     if (!s) return p ? SK_E_BADSESSION : SK_E_INVAL;
-    for (int32_t b : s->blocks) p->free_blocks.push_back(b);
-    p->blocks_in_use -= (int64_t)s->blocks.size();
+    for (int32_t b : s->blocks) release_block(p, b);
     s->blocks.clear(); s->len = 0; s->frozen = 0; s->win = 0; s->live = false;
     p->free_ids.push_back(id);
     return SK_OK;
@@ -904,9 +912,8 @@ int sk_session_truncate(sk_pool* p, int32_t id, int64_t new_length)
     const int64_t B = p->d.block_tokens;
     const size_t keep = size_t((s->len + B - 1) / B);
     while (s->blocks.size() > keep) {
-        p->free_blocks.push_back(s->blocks.back());
+        release_block(p, s->blocks.back());
         s->blocks.pop_back();
-        p->blocks_in_use--;
     }
     return SK_OK;
 }
@@ -936,9 +943,8 @@ int sk_session_evict_oldest(sk_pool* p, int32_t id, int64_t n_tokens, void* hip_
     const int64_t b0 = (s->frozen + B - 1) / B, b1 = s->win / B;
     if (b1 <= b0) return SK_OK;
     const int64_t k = b1 - b0;
-    for (int64_t b = b0; b < b1; ++b) p->free_blocks.push_back(s->blocks[(size_t)b]);
+    for (int64_t b = b0; b < b1; ++b) release_block(p, s->blocks[(size_t)b]);
     s->blocks.erase(s->blocks.begin() + b0, s->blocks.begin() + b1);
-    p->blocks_in_use -= k;
     s->win -= k * B; s->len -= k * B;
     if (!p->device || s->blocks.size() == (size_t)b0) return SK_OK;
     // rewrite the moved tail of the session's device block table (ordered on the caller's stream)
@@ -953,6 +959,59 @@ int sk_session_evict_oldest(sk_pool* p, int32_t id, int64_t n_tokens, void* hip_
     SK_HIP(hipMemcpyAsync(dev_tbl, host, bytes, hipMemcpyHostToDevice, st));
     SK_HIP(hipEventRecord(p->ring_ev[slot], st));
     p->ring_used[slot] = true;
+    return SK_OK;
+}
+
+int sk_session_fork(sk_pool* p, int32_t src_id, int64_t n_prefix, int32_t* out_id, void* hip_stream)
+{
+    if (!p || !out_id) return SK_E_INVAL;
+    Session* src = get_session(p, src_id);
+    if (!src) return SK_E_BADSESSION;
+    if (n_prefix < 0 || n_prefix > src->retained()) return SK_E_INVAL;
+    if (p->free_ids.empty()) return SK_E_NOMEM;
+    // storage layout of the new session: the same hole as the source if the prefix reaches behind it
+    const int64_t B = p->d.block_tokens;
+    int64_t frozen, win, len;
+    if (n_prefix <= src->frozen) frozen = win = len = n_prefix;
+    else { frozen = src->frozen; win = src->win; len = src->win + (n_prefix - src->frozen); }
+    const int64_t n_blk = (len + B - 1) / B;
+    const bool tail_partial = len % B != 0;      // the new session will write into its last block: it gets a copy
+    if (tail_partial && p->free_blocks.empty()) return SK_E_NOMEM;
+    const int32_t id = p->free_ids.back();
+    p->free_ids.pop_back();
+    Session& d = p->sessions[id];
+    d.live = true; d.frozen = frozen; d.win = win; d.len = len;
+    d.blocks.assign(src->blocks.begin(), src->blocks.begin() + n_blk);
+    for (int64_t i = 0; i < n_blk - (tail_partial ? 1 : 0); ++i) p->refcnt[(size_t)d.blocks[(size_t)i]]++;
+    int32_t tail_src = -1;
+    if (tail_partial) {
+        tail_src = d.blocks.back();
+        d.blocks.back() = p->free_blocks.front();
+        p->refcnt[(size_t)d.blocks.back()] = 1;
+        p->free_blocks.pop_front();
+        p->blocks_in_use++;
+    }
+    *out_id = id;
+    p->stats.forks++;
+    if (!p->device || n_blk == 0) return SK_OK;
+    hipStream_t st = (hipStream_t)hip_stream;
+    // the new session's block table, then the copy of the partly filled last block (all KV heads)
+    int slot; unsigned char* host;
+    int rc = ring_acquire(p, &slot, &host);
+    if (rc) return rc;
+    const size_t bytes = (size_t)n_blk * sizeof(int32_t);
+    if (bytes > kMetaBytes) return SK_E_WORKSPACE;
+    memcpy(host, d.blocks.data(), bytes);
+    int32_t* dev_tbl = (int32_t*)((unsigned char*)p->d.workspace + p->L.off_tables) + int64_t(id) * p->L.max_blocks_per_session;
+    SK_HIP(hipMemcpyAsync(dev_tbl, host, bytes, hipMemcpyHostToDevice, st));
+    SK_HIP(hipEventRecord(p->ring_ev[slot], st));
+    p->ring_used[slot] = true;
+    if (tail_partial) {
+        unsigned char* kv = (unsigned char*)p->d.kv_mem;
+        SK_HIP(hipMemcpy2DAsync(kv + int64_t(d.blocks.back()) * p->L.blk_stride, (size_t)p->L.head_stride,
+                                kv + int64_t(tail_src) * p->L.blk_stride, (size_t)p->L.head_stride,
+                                (size_t)p->L.blk_stride, (size_t)p->d.n_kv_heads, hipMemcpyDeviceToDevice, st));
+    }
     return SK_OK;
 }
 

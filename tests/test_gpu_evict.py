@@ -106,3 +106,35 @@ def test_eviction_in_batched_calls_and_truncate():
     ro, rl = ref.sessions[a].query(synth.to_raw(qq))
     compare("query after truncate into the frozen region", out, lse, ro, rl, shape.dtype)
     assert pool.sk_session_length(a) == 30
+
+
+@pytest.mark.parametrize("n_prefix", [512, 500, 37, 0, 1111])
+def test_fork_then_diverge(n_prefix):
+    """A forked session reads the shared prefix through the source's blocks; afterwards the two
+    sessions append different tokens, evict, query and are destroyed independently, each equal to
+    its own oracle session; cache bytes of both read back bit for bit."""
+    shape = synth.CFG2
+    gen = synth.generator(2, stream=50 + n_prefix)
+    pr = Pair(shape, block_tokens=16, n_blocks=300, kv_fill=0xFF, max_batch_tokens=2048)
+    a = pr.create()
+    q, k, v = synth.draw_qkv(gen, 1111, shape)
+    pr.append(a, q, k, v, check=False)
+    pr.freeze(a, 64)
+    b = pr.pool.sk_session_fork(a, n_prefix)
+    pr.oracles[b] = pr.oracles[a].fork(n_prefix)
+    assert pr.pool.sk_session_length(b) == n_prefix
+    pr.check_cache(b)
+    for rnd in range(2):
+        for sid, L in ((a, 130), (b, 257)):
+            q, k, v = synth.draw_qkv(gen, L, shape)
+            pr.append(sid, q, k, v, name="append to %s, round %d" % ("source" if sid == a else "fork", rnd))
+        qq, kq, vq = synth.draw_qkv(gen, 20, shape)
+        for sid in (a, b):
+            pr.query(sid, qq, name="query A"); pr.query(sid, qq, kq, vq, name="query B")
+        if pr.pool.sk_session_length(b) > 300:
+            pr.evict(b, 150)                              # the fork slides, the source does not
+        pr.check_cache(a); pr.check_cache(b)
+    pr.pool.sk_session_destroy(a)                         # the fork keeps the shared blocks alive
+    q, k, v = synth.draw_qkv(gen, 64, shape)
+    pr.append(b, q, k, v, name="append to the fork after the source is gone")
+    pr.check_cache(b)

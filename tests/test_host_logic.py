@@ -197,3 +197,45 @@ def test_eviction_metadata():
         p.sk_session_evict_oldest(a, 1)                 # nothing behind the frozen region
     st = p.sk_pool_get_stats()
     assert st["tokens_evicted"] == 44
+
+
+def test_fork_shares_blocks_by_reference_count():
+    """Fork = table copy + one block at most: full blocks of the prefix are shared, a partly filled
+    last block is replaced by a fresh one; a shared block returns to the free list only when its last
+    holder lets go, whichever way (destroy, truncate, evict)."""
+    p = meta_pool(n_blocks=12, block_tokens=16, max_sessions=4)
+    a = p.sk_session_create()
+    p.reserve(a, 70)                                     # blocks 0..4
+    b = p.sk_session_fork(a, 48)                         # three full blocks, shared
+    assert p.sk_session_block_table(b) == [0, 1, 2] and p.sk_session_length(b) == 48
+    assert p.sk_pool_blocks_free() == 7
+    c = p.sk_session_fork(a, 40)                         # 2 shared + a copy of the third
+    assert p.sk_session_block_table(c) == [0, 1, 5] and p.sk_pool_blocks_free() == 6
+    p.reserve(b, 10)                                     # b's next tokens go to a block of its own
+    assert p.sk_session_block_table(b) == [0, 1, 2, 6]
+    p.sk_session_destroy(a)                              # blocks 3, 4 free; 0, 1, 2 still held
+    assert p.sk_pool_blocks_free() == 7
+    p.sk_session_truncate(b, 16)                         # b drops 1, 2, 6: 2 and 6 free, 1 still held by c
+    assert p.sk_pool_blocks_free() == 9
+    p.sk_session_evict_oldest(c, 32)                     # c drops 0 and 1: 1 free now, 0 still held by b
+    assert p.sk_session_block_table(c) == [5] and p.sk_pool_blocks_free() == 10
+    p.sk_session_destroy(b)
+    p.sk_session_destroy(c)
+    assert p.sk_pool_blocks_free() == 12
+    # the hole travels with the prefix
+    a = p.sk_session_create()
+    p.reserve(a, 100)
+    p.sk_session_freeze(a, 10)
+    p.sk_session_evict_oldest(a, 25)                     # retained 75: [0,10) + storage [19,84) after dropping one block
+    d = p.sk_session_fork(a, 30)
+    assert p.sk_session_length(d) == 30
+    p.sk_session_evict_oldest(d, 20)
+    assert p.sk_session_length(d) == 10
+    with pytest.raises(sk.SkError):
+        p.sk_session_evict_oldest(d, 1)                  # only the frozen tokens are left
+    with pytest.raises(sk.SkError) as e:
+        p.sk_session_fork(a, 76)
+    assert e.value.status == sk.SK_E_INVAL
+    e2 = p.sk_session_fork(a, 0)
+    assert p.sk_session_length(e2) == 0 and p.sk_session_block_table(e2) == []
+    assert p.sk_pool_get_stats()["forks"] == 4

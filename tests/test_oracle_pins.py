@@ -435,3 +435,26 @@ def test_eviction_attends_over_frozen_prefix_and_retained_window_only():
         s.evict_oldest(s.length - nf + 1)              # more than Region 1 holds
     with pytest.raises(ValueError):
         s.freeze(nf - 1)                               # the frozen region only grows
+
+
+def test_fork_is_a_prefix_by_value():
+    """fork(n) reads like the source cut at n tokens (brute force on the first n tokens), and the
+    two sessions are isolated afterwards (Sec. 3.4 "isolation between sessions")."""
+    Hq, Hkv, d, n, n_prefix = 2, 2, 3, 9, 6
+    rng = np.random.default_rng(12)
+    K, V = _rand(rng, (n, Hkv, d), "f32"), _rand(rng, (n, Hkv, d), "f32")
+    q = _rand(rng, (1, Hq, d), "f32")
+    s = OracleSession("f32", Hq, Hkv, d)
+    s.append(np.zeros((n, Hq, d), np.float32), K, V)
+    t = s.fork(n_prefix)
+    o, l = t.query(q)
+    for h in range(Hq):
+        ro, rl = _brute_row(q[0, h].tolist(), [K[j, h].tolist() for j in range(n_prefix)],
+                            [V[j, h].tolist() for j in range(n_prefix)], 1.0 / math.sqrt(d))
+        np.testing.assert_allclose(o[0, h], ro, rtol=1e-12, atol=1e-13)
+        assert abs(l[0, h] - rl) < 1e-12
+    before = s.query(q)
+    t.append(_rand(rng, (2, Hq, d), "f32"), _rand(rng, (2, Hkv, d), "f32"), _rand(rng, (2, Hkv, d), "f32"))
+    t.evict_oldest(3)
+    np.testing.assert_array_equal(s.query(q)[0], before[0])
+    assert s.length == n and t.length == n_prefix + 2 - 3
