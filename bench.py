@@ -146,6 +146,7 @@ def main():
         extras["cfg4_multi_tenant_step"] = multi_tenant(sk)
         extras["sliding_window_32k"] = sliding_window(sk)
         extras["fork_cost"] = fork_cost(sk)
+        extras["top2_sampling"] = top2_sampling(sk)
         res["extras"] = extras
     if not args.no_cpu_baseline:
         rows = args.cpu_rows or ((L + nq) * shape.n_q_heads if n <= 32768 else 4096)
@@ -310,6 +311,29 @@ def fork_cost(sk, n=32768 + 7, reps=20):
     res["bytes_per_fork_at_32775"] = {"block_table": 4 * ((n + B - 1) // B), "block_copy": B * shape.kv_bytes_per_token,
                                       "kv_shared_not_copied": (n // B) * B * shape.kv_bytes_per_token}
     pool.close()
+    return res
+
+
+def top2_sampling(sk, vocab=128256, reps=50):
+    """sk_top2 (greedy token, runner-up and logit gap per row) over synthetic fp32 logits N(0, 2.5):
+    64 rows (the answers of a question batch) and 1,024 rows (enough bytes to see the rate)."""
+    res = {"vocab": vocab}
+    gen = synth.generator(6, stream=1)
+    for rows in (64, 1024):
+        x = (2.5 * synth.draw(gen, (rows, vocab), "f32")).cuda()
+        ws = torch.empty(sk.lib().sk_top2_workspace_bytes(rows, vocab), dtype=torch.uint8, device="cuda")
+        for _ in range(5):
+            sk.sk_top2(x, workspace=ws)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            sk.sk_top2(x, workspace=ws)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        res["rows_%d" % rows] = {"us_per_call": us, "GBps": rows * vocab * 4 / (us * 1e-6) / 1e9,
+                                 "hbm_frac": rows * vocab * 4 / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS}
+    res["timing"] = "torch events on the launch stream around back-to-back calls (two kernels each), output allocation included"
     return res
 
 

@@ -219,6 +219,24 @@ int sk_session_evict_oldest(sk_pool* pool, int32_t id, int64_t n_tokens, void* h
  */
 int sk_session_fork(sk_pool* pool, int32_t src, int64_t n_prefix, int32_t* out_id, void* hip_stream);
 
+/*
+ * GREEDY SAMPLING WITH A CONFIDENCE GAP (Sec. 3.8 on-device greedy sampling: the argmax of a
+ * ~128k-entry logit row is taken on the device instead of copying the row to the host;
+ * Sec. 3.9.2 confidence gamma = top-1 logit - top-2 logit; Sec. 3.9.4 Delta_ready).
+ * Independent of any pool.  logits: DEVICE float32 [rows][row_stride], the first `vocab` entries
+ * of a row count; 16-byte aligned, row_stride a multiple of 4, vocab >= 2, rows <= 65535.
+ * Outputs, DEVICE, one per row: idx1 = lowest index of the row maximum, idx2 = lowest index of
+ * the maximum among the other entries (int32); val1, val2 = those logits, gap = val1 - val2 in
+ * fp32 (each of the three may be NULL).  Equal logits: the lower index comes first (the paper
+ * does not say).  Logits are assumed not to be NaN.
+ * workspace: DEVICE scratch of sk_top2_workspace_bytes(rows, vocab) bytes, 16-byte aligned,
+ * owned by the caller (the library allocates nothing); too small gives SK_E_WORKSPACE.
+ */
+size_t sk_top2_workspace_bytes(int32_t rows, int32_t vocab);
+int sk_top2(const float* logits, int32_t rows, int32_t vocab, int64_t row_stride,
+            void* workspace, size_t workspace_bytes,
+            int32_t* idx1, int32_t* idx2, float* val1, float* val2, float* gap, void* hip_stream);
+
 /* Byte offset inside kv_mem of element (block, kv_head, is_v, slot, dim), so a harness can
  * address the pool without knowing the layout.  Negative on bad arguments. */
 int64_t sk_pool_element_offset(const sk_pool* pool, int64_t block, int32_t kv_head, int32_t is_v,

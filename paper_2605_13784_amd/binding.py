@@ -63,7 +63,7 @@ EXPORTS = [
     "sk_session_truncate", "sk_session_freeze", "sk_session_evict_oldest", "sk_session_fork",
     "sk_pool_set_profiling", "sk_pool_read_profile",
     "sk_pool_element_offset", "sk_pool_get_stats", "sk_pool_last_launch", "sk_strerror",
-    "sk_last_hip_error", "sk_version",
+    "sk_last_hip_error", "sk_version", "sk_top2_workspace_bytes", "sk_top2",
 ]
 
 _lib = None
@@ -105,6 +105,9 @@ def lib():
     L.sk_session_freeze.argtypes = [vp, i32, i64]
     L.sk_session_evict_oldest.argtypes = [vp, i32, i64, vp]
     L.sk_session_fork.argtypes = [vp, i32, i64, P(i32), vp]
+    L.sk_top2_workspace_bytes.restype = ctypes.c_size_t
+    L.sk_top2_workspace_bytes.argtypes = [i32, i32]
+    L.sk_top2.argtypes = [vp, i32, i32, i64, vp, ctypes.c_size_t, vp, vp, vp, vp, vp, vp]
     L.sk_pool_set_profiling.argtypes = [vp, ctypes.c_int]
     L.sk_pool_read_profile.argtypes = [vp, P(sk_profile), P(ctypes.c_float), P(ctypes.c_float), i32]
     L.sk_pool_element_offset.restype = i64
@@ -346,3 +349,21 @@ class Pool:
         v = torch.empty_like(k)
         _ck(lib().sk_session_gather(self.h, sid, first, count, _p(k), _p(v), _stream(stream)), "sk_session_gather")
         return k, v
+
+
+def sk_top2(logits, stream=None, workspace=None):
+    """logits: CUDA float32 tensor [rows, vocab] (rows may be strided by a multiple of 4 elements).
+    Returns (idx1, idx2, val1, val2, gap), each [rows]."""
+    assert logits.is_cuda and logits.dtype == torch.float32 and logits.dim() == 2 and logits.stride(1) == 1
+    rows, vocab = logits.shape
+    need = lib().sk_top2_workspace_bytes(rows, vocab)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=logits.device)
+    idx1 = torch.empty(rows, dtype=torch.int32, device=logits.device)
+    idx2 = torch.empty_like(idx1)
+    val1 = torch.empty(rows, dtype=torch.float32, device=logits.device)
+    val2 = torch.empty_like(val1)
+    gap = torch.empty_like(val1)
+    _ck(lib().sk_top2(ctypes.c_void_p(logits.data_ptr()) if rows else None, rows, vocab, logits.stride(0) if rows else vocab, _p(workspace),
+                      workspace.numel(), _p(idx1), _p(idx2), _p(val1), _p(val2), _p(gap), _stream(stream)), "sk_top2")
+    return idx1, idx2, val1, val2, gap

@@ -21,7 +21,7 @@ def meta_pool(**kw):
 
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "sk.h")).read()
-    declared = set(re.findall(r"\b(sk_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(sk_[a-z0-9_]+)\s*\(", header))
     declared -= {"sk_pool_desc", "sk_pool_stats", "sk_launch_info", "sk_status", "sk_pool", "sk_profile"}
     assert declared == set(sk.EXPORTS)
     L = sk.lib()
