@@ -55,6 +55,9 @@ struct sk_work {
     int32_t eph_pos0[2];  // absolute position of its first token
     int32_t hole_lo;      // cached tokens [hole_lo, hole_hi) are evicted (Region-1 FIFO eviction): their
     int32_t hole_hi;      // blocks are still streamed, the keys never attended to; empty when lo == hi
+    int32_t tok_period;   // > 0: the tile packs sequences of tok_period tokens each, all starting at pos0;
+    int32_t sub_blocks;   // sequence k's second uncommitted segment starts at staging block eph_blk[1] + k * sub_blocks
+    int32_t pad[2];
 };
 
 // One row tile of the cross-split combine.

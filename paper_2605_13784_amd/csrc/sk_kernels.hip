@@ -73,6 +73,7 @@ __device__ __forceinline__ bool sk_decode_work(const sk_launch& P, int b, sk_wor
     }
     w.part = (P.n_splits == 1) ? -1 : (tile * P.n_splits + split) * Hkv + head;
     w.hole_lo = P.hole_lo; w.hole_hi = P.hole_hi;
+    w.tok_period = 0; w.sub_blocks = 0;
     for (int i = 0; i < 2; ++i) {
         w.eph_blk[i] = P.eph_blk[i]; w.eph_cnt[i] = eph_part ? P.eph_cnt[i] : 0; w.eph_pos0[i] = P.eph_pos0[i];
     }
@@ -92,6 +93,8 @@ struct sk_seg {
     int32_t hole_lo, hole_n;     // tokens [hole_lo, hole_lo + hole_n) are evicted: streamed, never attended to
 };
 
+// Segment s of a work item: 0 = cached tokens, 1 = first uncommitted segment, 2 + k = second
+// uncommitted segment of sub-sequence k (k = 0 unless the tile packs several sequences).
 __device__ __forceinline__ sk_seg sk_make_seg(const sk_launch& P, const sk_work& w, int s)
 {
     sk_seg g;
@@ -103,7 +106,7 @@ __device__ __forceinline__ sk_seg sk_make_seg(const sk_launch& P, const sk_work&
         g.hole_lo = w.hole_lo; g.hole_n = w.hole_hi - w.hole_lo;
     } else {
         g.base = P.g.eph + (int64_t)w.kv_head * P.g.eph_head_stride;
-        g.table = P.g.eph_ident + (s == 1 ? w.eph_blk[0] : w.eph_blk[1]); g.blk_stride = P.g.eph_blk_stride;
+        g.table = P.g.eph_ident + (s == 1 ? w.eph_blk[0] : w.eph_blk[1] + (s - 2) * w.sub_blocks); g.blk_stride = P.g.eph_blk_stride;
         g.v_off = P.g.eph_v_off; g.B = 16; g.log2B = 4;
         g.begin = 0; g.end = (s == 1 ? w.eph_cnt[0] : w.eph_cnt[1]); g.pos_shift = (s == 1 ? w.eph_pos0[0] : w.eph_pos0[1]);
         g.hole_lo = 0; g.hole_n = 0;
@@ -306,9 +309,16 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
     if (wave_tok_last > w.n_tok - 1) wave_tok_last = w.n_tok - 1;
     const bool wave_has_rows = wave_tok_first < w.n_tok;
     const bool causal = w.pos0 < SK_NO_CAUSAL;
-    const int p_row = causal ? w.pos0 + (row_valid ? tok_local : wave_tok_last) : 0x7fffffff;
-    const int p_wave_min = causal ? w.pos0 + wave_tok_first : 0x7fffffff;
-    const int p_wave_max = causal ? w.pos0 + wave_tok_last : 0x7fffffff;
+    // A tile may pack several sequences of tok_period tokens each (questions of a batch): token t of
+    // the tile is token t % tok_period of sequence t / tok_period, all sequences start at pos0, and
+    // each has its own second uncommitted segment.  A wave's rows belong to one sequence (the host
+    // only packs when 32 rows divide a sequence's rows).
+    const unsigned period = w.tok_period > 0 ? (unsigned)w.tok_period : 0x7fffffffu;
+    const int n_sub = w.tok_period > 0 ? (w.n_tok + w.tok_period - 1) / w.tok_period : 1;
+    const int wave_sub = (int)((unsigned)wave_tok_first / period);
+    const int p_row = causal ? w.pos0 + (int)((unsigned)(row_valid ? tok_local : wave_tok_last) % period) : 0x7fffffff;
+    const int p_wave_min = causal ? w.pos0 + (int)((unsigned)wave_tok_first % period) : 0x7fffffff;
+    const int p_wave_max = causal ? w.pos0 + (int)((unsigned)wave_tok_last % period) : 0x7fffffff;
 
     // Q^T operand: lane (row r, k-group kg) keeps Q[row][16*ks + 8*kg .. +7] for ks = 0..7
     bf16x8 qreg[8];
@@ -348,13 +358,14 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
     }
 
 #pragma unroll 1
-    for (int s = 0; s < 3; ++s) {
+    for (int s = 0; s < 2 + n_sub; ++s) {
         sk_seg g = sk_make_seg(P, w, s);
         if (g.end <= g.begin) continue;
         const int ntiles = (g.end - g.begin + SK_TILE - 1) / SK_TILE;
         const int niter = (ntiles + TPI - 1) / TPI;
         const int last_group = (g.end - 1) & ~15;
-        const int seg_last_pos = g.end - 1 + g.pos_shift;
+        // last position of the segment this wave's rows may see; nothing of another sequence's segment
+        const int seg_last_pos = (s >= 2 && s - 2 != wave_sub) ? (int)0x80000000 : g.end - 1 + g.pos_shift;
         const int lim_wave_min = p_wave_min < seg_last_pos ? p_wave_min : seg_last_pos;
         const int lim_wave_max = p_wave_max < seg_last_pos ? p_wave_max : seg_last_pos;
         const int lim_row = p_row < seg_last_pos ? p_row : seg_last_pos;

@@ -357,6 +357,7 @@ struct TileReq {            // one tile of query rows and the keys it may see
     int32_t kv_vis;         // cached tokens visible to the tile (positions 0 .. kv_vis-1)
     int32_t eph_blk[2], eph_cnt[2], eph_pos0[2];
     int32_t hole_lo, hole_hi;   // evicted cached tokens of the session
+    int32_t tok_period, sub_blocks;   // > 0: the tile packs sequences of tok_period tokens (see sk_work)
 };
 struct ListGroup {          // tiles that share a kernel variant and the q/out/lse arrays
     Variant v = {SK_KV_SIMPLE, 16, 1};
@@ -432,6 +433,7 @@ int run_list(sk_pool* p, ScatterBatch* sb, int n_sb, ListGroup* groups, int n_gr
                             w.kv_end = int32_t(std::min<int64_t>(t.kv_vis, (part + 1) * chunk));
                             w.part = np > 1 ? slot0[i - i0] + part * Hkv + h : -1;
                             w.hole_lo = t.hole_lo; w.hole_hi = t.hole_hi;
+                            w.tok_period = t.tok_period; w.sub_blocks = t.sub_blocks;
                             if (part == np - 1)
                                 for (int e = 0; e < 2; ++e) { w.eph_blk[e] = t.eph_blk[e]; w.eph_cnt[e] = t.eph_cnt[e]; w.eph_pos0[e] = t.eph_pos0[e]; }
                             work[gi].push_back(w);
@@ -861,15 +863,29 @@ int sk_session_query_shared_prefix(sk_pool* p, int32_t id, const void* qp, const
         sb[1].k = ks; sb[1].v = vs;
         pick_variant(p, Sfx, groups[1].v);
         groups[1].q = qs; groups[1].out = out_suffix; groups[1].lse = lse_suffix;
-        for (int32_t j = 0; j < NQ; ++j) {
-            const int64_t blk = pre_blocks + j * sfx_blocks;
-            build_scatter(p, nullptr, id, 0, j * Sfx, Sfx, 0, true, blk, sb[1].items);
+        // Short suffixes are packed: several questions share one 256-row tile of the eight-wave
+        // kernel (their rows see the same cache and prefix; each sees its own suffix), when a
+        // question's rows are a multiple of a wave's 32 and divide 256.
+        const int64_t rows_q = int64_t(Sfx) * p->L.G;
+        const char* no_pack = getenv("SK_NO_PACK");
+        const bool pack = groups[1].v.id != SK_KV_SIMPLE && rows_q < 256 && rows_q % 32 == 0 && 256 % rows_q == 0 && NQ > 1 &&
+                          !(no_pack && no_pack[0] == '1');
+        const int32_t per_tile = pack ? int32_t(256 / rows_q) : 1;
+        if (pack) groups[1].v = Variant{SK_KV_MFMA256, 256, 256 / p->L.G};
+        for (int32_t j = 0; j < NQ; ++j)
+            build_scatter(p, nullptr, id, 0, j * Sfx, Sfx, 0, true, pre_blocks + j * sfx_blocks, sb[1].items);
+        for (int32_t j = 0; j < NQ; j += per_tile) {
+            const int32_t nq_tile = std::min(per_tile, NQ - j);
             TileReq base = {};
             base.tbl_off = tbl_off; base.pos0 = int32_t(n + P); base.kv_vis = (int32_t)n;
             base.hole_lo = (int32_t)s->frozen; base.hole_hi = (int32_t)s->win;
             base.eph_blk[0] = 0; base.eph_cnt[0] = P; base.eph_pos0[0] = (int32_t)n;
-            base.eph_blk[1] = (int32_t)blk; base.eph_cnt[1] = Sfx; base.eph_pos0[1] = int32_t(n + P);
-            add_tiles(groups[1], base, j * Sfx, Sfx);
+            base.eph_blk[1] = int32_t(pre_blocks + j * sfx_blocks); base.eph_cnt[1] = Sfx; base.eph_pos0[1] = int32_t(n + P);
+            if (pack) {
+                base.tok_period = Sfx; base.sub_blocks = (int32_t)sfx_blocks;
+                base.q_tok0 = j * Sfx; base.n_tok = nq_tile * Sfx;
+                groups[1].tiles.push_back(base);
+            } else add_tiles(groups[1], base, j * Sfx, Sfx);
         }
     }
     return run_list(p, sb, 2, groups, 2, out_dtype, (hipStream_t)hip_stream);
