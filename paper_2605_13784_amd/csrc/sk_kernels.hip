@@ -248,12 +248,8 @@ __device__ __forceinline__ void sk_issue_tile(const sk_seg& g, int t0, int last_
 
 #ifdef SK_EXPERIMENT              // development builds: P.pad bit 0 = no arithmetic, bit 1 = no loads
 #define SK_EXP_LOADS if (!(P.pad & 2))
-// bit 6: waves 0 and 4 of workgroup 0 record the cycle counter at slot boundaries
-#define SK_STAMP() do { if ((P.pad & 64) && blockIdx.x == 0 && lane == 0 && (wave & 3) == 0 && stamp_n < 1024) \
-        ((long long*)P.work)[(wave >> 2) * 1024 + stamp_n++] = clock64(); } while (0)
 #else
 #define SK_EXP_LOADS
-#define SK_STAMP() do { } while (0)
 #endif
 
 template <int NRG, int NPH, int NSS>
@@ -278,23 +274,14 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
     if (P.pad & 4) return;                     // launch overhead only
 #endif
     const unsigned lds_base = (unsigned)(uintptr_t)(sk_lds_ptr)lds;   // LDS byte address of the ring
-#ifdef SK_EXPERIMENT
-    int stamp_n = 0;
-    if ((P.pad & 64) && blockIdx.x == 0 && threadIdx.x == 0) { ((long long*)P.work)[2048] = clock64(); ((long long*)P.work)[2049] = wall_clock64(); }
-#endif
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // in a scalar register
     const int rg = wave % NRG, ph = wave / NRG;
     // Eight waves work as two groups of four that alternate between the matrix pipe and the vector
     // ALU (see the segment loop).  Waves i and i + 4 of a workgroup share a SIMD, so a SIMD holds
     // one wave of each group.  `sub` is the wave's index among the four that load a tile.
-#ifdef SK_EXPERIMENT
-    const int grp = NW == 8 ? ((P.pad & 32) ? (wave & 1) : (wave >> 2)) : 0;
-    const int sub = NW == 8 ? ((P.pad & 32) ? (wave >> 1) : (wave & 3)) : wave;
-#else
     const int grp = NW == 8 ? (wave >> 2) : 0;
     const int sub = wave & 3;
-#endif
     const unsigned unit_base = lds_base + sub * US;                // LDS address of this wave's unit of ring slot 0, tile 0
     const int r = lane & 31, kg = lane >> 5;
     const int log2G = P.g.log2G, G = P.g.G;
@@ -519,15 +506,8 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
                 if (NSS == 2 || later <= 0) SK_WAIT_VMCNT(0);
                 else if (later == 1) SK_WAIT_VMCNT(LPW);
                 else SK_WAIT_VMCNT(2 * LPW);
-#ifdef SK_EXPERIMENT
-                if (!(P.pad & 128))                 // bit 7: no barrier in the loop
-#endif
                 sk_lds_barrier();
-                bool do_refill = it + NSS - 1 < niter;
-#ifdef SK_EXPERIMENT
-                if (P.pad & 256) do_refill = false;     // bit 8: no refill code at all (addresses, table lookups)
-#endif
-                if (do_refill) {
+                if (it + NSS - 1 < niter) {
 #pragma unroll
                     for (int p = 0; p < TPI; ++p)
                         SK_EXP_LOADS sk_issue_tile<US>(g, g.begin + ((it + NSS - 1) * TPI + p) * SK_TILE, last_group, nb[p],
@@ -691,19 +671,12 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks) kc[ks] = kptr[ks] + (j & 3) * 1024;
                 if (grp == 0) wait_iteration(j);
-                SK_STAMP();
                     sk_lds_barrier();                                  // barrier 2j (group 0), 2j+1 (group 1)
-                SK_STAMP();
                 matrix_slot(sk_int<1>{}, j, kc, vp);
-                SK_STAMP();
                 if (grp == 1 && j + 1 < niter) wait_iteration(j + 1);
-                SK_STAMP();
                 sk_lds_barrier();                                  // barrier 2j+1 (group 0), 2j+2 (group 1)
-                SK_STAMP();
                 refill(j);
-                SK_STAMP();
                 vector_slot(j, vc);
-                SK_STAMP();
             }
             // slots after the last iteration: P V only
             sk_lds_barrier();
@@ -713,9 +686,6 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
         }
     }
 
-#ifdef SK_EXPERIMENT
-    if ((P.pad & 64) && blockIdx.x == 0 && threadIdx.x == 0) { ((long long*)P.work)[2050] = clock64(); ((long long*)P.work)[2051] = wall_clock64(); }
-#endif
     float l_tot; { const sk_halves h = sk_both_halves(l_run); l_tot = h.lo + h.hi; }
 
     if (NPH > 1) {

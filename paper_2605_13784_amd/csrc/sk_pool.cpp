@@ -259,7 +259,6 @@ int run_regular(sk_pool* p, int32_t id, const void* q, int64_t n_tok, int32_t po
     L.hole_lo = (int32_t)p->sessions[id].frozen; L.hole_hi = (int32_t)p->sessions[id].win;
 #ifdef SK_EXPERIMENT
     if (const char* x = getenv("SK_EXPERIMENT")) L.pad = atoi(x);
-    if (const char* x = getenv("SK_DEBUG_PTR")) L.work = (const sk_work*)strtoull(x, nullptr, 0);
 #endif
     const int32_t wgs = int32_t(base_wgs * parts);
     hipEvent_t* pe = prof_begin(p, st);
