@@ -78,6 +78,10 @@ struct sk_scatter {
     int32_t block_id;
 };
 
+// A short scatter list that travels in the kernel arguments.
+#define SK_SCATTER_ARGS_MAX 80
+struct sk_scatter_list { sk_scatter item[SK_SCATTER_ARGS_MAX]; };
+
 enum { SK_MODE_REGULAR = 0, SK_MODE_LIST = 1 };
 // attention kernel variants: fp32-FMA kernel; bf16 MFMA kernel with 128-, 64- and 256-row tiles
 enum { SK_KV_SIMPLE = 0, SK_KV_MFMA128 = 1, SK_KV_MFMA64 = 2, SK_KV_MFMA256 = 3 };
@@ -107,6 +111,9 @@ struct sk_launch {
 int sk_launch_scatter(const sk_geom& g, const void* k, const void* v, const sk_scatter* items,
                       int32_t n_items, int32_t* tables_rw, unsigned char* kv_rw,
                       unsigned char* eph_rw, void* stream);
+int sk_launch_scatter_args(const sk_geom& g, const void* k, const void* v, const sk_scatter_list& items,
+                           int32_t n_items, int32_t* tables_rw, unsigned char* kv_rw,
+                           unsigned char* eph_rw, void* stream);
 int sk_launch_attention(const sk_launch& L, int variant, int32_t n_workgroups, void* stream);
 int sk_launch_combine(const sk_launch& L, int32_t n_row_tiles, void* stream);
 int sk_launch_gather(const sk_geom& g, int32_t tbl_off, int64_t first, int64_t count,

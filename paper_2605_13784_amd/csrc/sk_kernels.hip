@@ -997,13 +997,10 @@ __global__ __launch_bounds__(256) void sk_combine(const sk_launch P)
 // integer lanes.  K rows are copied as 16-byte chunks; V is copied likewise for f32 pools and
 // transposed through LDS for bf16 pools ([dim][token]).
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void sk_scatter_kernel(const sk_geom g, const void* k, const void* v,
-                                                         const sk_scatter* items, int32_t* tables_rw,
-                                                         unsigned char* kv_rw, unsigned char* eph_rw)
+__device__ __forceinline__ void sk_scatter_item(const sk_geom& g, const void* k, const void* v, const sk_scatter& it,
+                                                const int head, int32_t* tables_rw, unsigned char* kv_rw, unsigned char* eph_rw)
 {
     __shared__ uint16_t vt[16][128 + 2];
-    const int item = blockIdx.x / g.Hkv, head = blockIdx.x % g.Hkv;
-    const sk_scatter it = items[item];
     const int tid = threadIdx.x;
     const int d = g.d, elem = g.elem;
     const int rowbytes = d * elem;
@@ -1059,6 +1056,23 @@ __global__ __launch_bounds__(256) void sk_scatter_kernel(const sk_geom g, const 
     }
 }
 
+// Items read from a list in the workspace (batched steps) ...
+__global__ __launch_bounds__(256) void sk_scatter_kernel(const sk_geom g, const void* k, const void* v,
+                                                         const sk_scatter* items, int32_t* tables_rw,
+                                                         unsigned char* kv_rw, unsigned char* eph_rw)
+{
+    const sk_scatter it = items[blockIdx.x / g.Hkv];
+    sk_scatter_item(g, k, v, it, blockIdx.x % g.Hkv, tables_rw, kv_rw, eph_rw);
+}
+// ... or carried in the kernel arguments (single-session calls: no host-to-device copy in front)
+__global__ __launch_bounds__(256) void sk_scatter_kernel_args(const sk_geom g, const void* k, const void* v,
+                                                              const sk_scatter_list items, int32_t* tables_rw,
+                                                              unsigned char* kv_rw, unsigned char* eph_rw)
+{
+    sk_scatter_item(g, k, v, items.item[blockIdx.x / g.Hkv], blockIdx.x % g.Hkv, tables_rw, kv_rw, eph_rw);
+}
+
+
 // Reads committed K/V back in token order (bit copy).  One thread per element pair is enough:
 // this is a verification / export path.
 __global__ __launch_bounds__(256) void sk_gather_kernel(const sk_geom g, int32_t tbl_off, int64_t first,
@@ -1092,6 +1106,16 @@ int sk_launch_scatter(const sk_geom& g, const void* k, const void* v, const sk_s
 {
     if (n_items <= 0) return 0;
     hipLaunchKernelGGL(sk_scatter_kernel, dim3(n_items * g.Hkv), dim3(256), 0, (hipStream_t)stream,
+                       g, k, v, items, tables_rw, kv_rw, eph_rw);
+    return (int)hipGetLastError();
+}
+
+int sk_launch_scatter_args(const sk_geom& g, const void* k, const void* v, const sk_scatter_list& items,
+                           int32_t n_items, int32_t* tables_rw, unsigned char* kv_rw, unsigned char* eph_rw,
+                           void* stream)
+{
+    if (n_items <= 0) return 0;
+    hipLaunchKernelGGL(sk_scatter_kernel_args, dim3(n_items * g.Hkv), dim3(256), 0, (hipStream_t)stream,
                        g, k, v, items, tables_rw, kv_rw, eph_rw);
     return (int)hipGetLastError();
 }

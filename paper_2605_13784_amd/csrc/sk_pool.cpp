@@ -309,6 +309,16 @@ int build_scatter(const sk_pool* p, const Session* s, int32_t id, int64_t dst_to
 int upload_and_scatter(sk_pool* p, const std::vector<sk_scatter>& items, const void* k, const void* v, hipStream_t st)
 {
     if (items.empty()) return SK_OK;
+    unsigned char* ws0 = (unsigned char*)p->d.workspace;
+    if (items.size() <= SK_SCATTER_ARGS_MAX) {          // short list: in the kernel arguments, nothing to upload
+        sk_scatter_list lst;
+        memcpy(lst.item, items.data(), items.size() * sizeof(sk_scatter));
+        int e = sk_launch_scatter_args(p->geom, k, v, lst, (int32_t)items.size(), (int32_t*)(ws0 + p->L.off_tables),
+                                       (unsigned char*)p->d.kv_mem, ws0 + p->L.off_eph, st);
+        if (e) { g_last_hip = e; return SK_E_HIP; }
+        p->stats.launches++;
+        return SK_OK;
+    }
     const size_t bytes = items.size() * sizeof(sk_scatter);
     if (bytes > kMetaBytes) return SK_E_WORKSPACE;
     int slot; unsigned char* host;
