@@ -97,10 +97,12 @@ def test_bf16_output_dtype_bf16_and_no_lse():
 
 @pytest.mark.parametrize("shape", [synth.Shape("bf16", 8, 8, 64), synth.Shape("bf16", 12, 4, 128),
                                    synth.Shape("f32", 8, 2, 128), synth.Shape("bf16", 64, 8, 128),
-                                   synth.Shape("bf16", 8, 8, 128)])
+                                   synth.Shape("bf16", 8, 8, 128), synth.Shape("bf16", 32, 2, 128),
+                                   synth.Shape("bf16", 32, 1, 128)])
 def test_other_shapes(shape):
     """head_dim 64 and a group size that is not a power of two go through the fp32-FMA kernel;
-    G = 8 and G = 1 go through the MFMA kernel."""
+    G = 32, 16, 8 and 1 go through the MFMA kernel (a wave's 32 rows are then one token's heads,
+    two tokens, four tokens, 32 tokens)."""
     gen = synth.generator(9, stream=shape.n_q_heads)
     pr = Pair(shape, n_blocks=64)
     sid = pr.create()
