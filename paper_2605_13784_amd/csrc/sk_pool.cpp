@@ -397,13 +397,34 @@ int run_list(sk_pool* p, ScatterBatch* sb, int n_sb, ListGroup* groups, int n_gr
     if (n_groups > kMaxGroups) return SK_E_INVAL;
     const int Hkv = p->d.n_kv_heads;
     int64_t kv_total = 0, n_tiles = 0;
+    int64_t kv_group[kMaxGroups] = {};
     for (int gi = 0; gi < n_groups; ++gi)
-        for (const TileReq& t : groups[gi].tiles) { kv_total += t.kv_vis; ++n_tiles; }
+        for (const TileReq& t : groups[gi].tiles) { kv_total += t.kv_vis; kv_group[gi] += t.kv_vis; ++n_tiles; }
     if (n_tiles == 0) return SK_OK;
-    // one chunk length for the whole step, so that workgroups cost about the same
-    const int64_t target = 4 * int64_t(p->target_wgs);
-    int64_t chunk = std::max<int64_t>(256, (kv_total * Hkv + target - 1) / target);
-    chunk = (chunk + 63) / 64 * 64;
+    // One chunk length per group (= per launch), so that the workgroups of a launch cost about the
+    // same whatever the session length, and every launch has enough of them to fill the chip
+    // several times over (rounds of one 512-thread workgroup per CU, or of two 256-thread ones).
+    int64_t chunk_g[kMaxGroups];
+    for (int gi = 0; gi < n_groups; ++gi) {
+        const int64_t per_round = groups[gi].v.id == SK_KV_MFMA256 ? 256 : 512;
+        const int64_t target = 4 * int64_t(p->target_wgs);       // 2,048 by default: 8 rounds of 256, 4 of 512
+        chunk_g[gi] = std::max<int64_t>(256, (kv_group[gi] * Hkv + target - 1) / target);
+        chunk_g[gi] = (chunk_g[gi] + 63) / 64 * 64;
+        // Workgroups of a launch run in rounds of `per_round`; pick, near that length, the one whose
+        // last round is fullest (a launch of 7.1 rounds takes as long as one of 8).
+        auto count_wgs = [&](int64_t c) {
+            int64_t n = 0;
+            for (const TileReq& t : groups[gi].tiles) n += std::max<int64_t>(1, (t.kv_vis + c - 1) / c);
+            return n * Hkv;
+        };
+        double best_eff = -1.0; int64_t best = chunk_g[gi];
+        for (int64_t c = std::max<int64_t>(256, chunk_g[gi] * 3 / 4 / 64 * 64); c <= chunk_g[gi] * 5 / 4; c += 64) {
+            const int64_t n = count_wgs(c);
+            const double eff = double(n) / double((n + per_round - 1) / per_round * per_round);
+            if (eff >= best_eff) { best_eff = eff; best = c; }       // ties: the longer chunk (fewer partials)
+        }
+        chunk_g[gi] = best;
+    }
     const int64_t cap_rows = p->L.part_slots * kPartSlotRows;
     std::vector<sk_work> work[kMaxGroups];
     std::vector<sk_comb> comb[kMaxGroups];
@@ -413,6 +434,7 @@ int run_list(sk_pool* p, ScatterBatch* sb, int n_sb, ListGroup* groups, int n_gr
         bool ok = true;
         for (int gi = 0; gi < n_groups && ok; ++gi) {
             ListGroup& g = groups[gi];
+            const int64_t chunk = chunk_g[gi];
             work[gi].clear(); comb[gi].clear();
             rows_base[gi] = rows_used;
             int64_t slot = 0;       // in units of this group's rows_per_slot, from rows_base
@@ -467,8 +489,8 @@ int run_list(sk_pool* p, ScatterBatch* sb, int n_sb, ListGroup* groups, int n_gr
         for (int gi = 0; gi < n_groups; ++gi)
             bytes += align_up(work[gi].size() * sizeof(sk_work), 256) + align_up(comb[gi].size() * sizeof(sk_comb), 256);
         if (ok && bytes <= kMetaBytes) break;
-        if (chunk > (int64_t(1) << 30)) return SK_E_WORKSPACE;
-        chunk *= 2;
+        if (chunk_g[0] > (int64_t(1) << 30)) return SK_E_WORKSPACE;
+        for (int gi = 0; gi < n_groups; ++gi) chunk_g[gi] *= 2;
     }
     // one upload: scatter lists, work lists, combine lists
     int slot; unsigned char* host;
