@@ -5,6 +5,7 @@ a call fails, an exception is raised.
 """
 import ctypes
 import os
+import numpy as np
 
 import torch
 
@@ -221,8 +222,9 @@ class Pool:
         return out.value
 
     def sk_pool_set_alloc_order(self, perm):
-        arr = (ctypes.c_int32 * len(perm))(*[int(x) for x in perm])
-        _ck(lib().sk_pool_set_alloc_order(self.h, arr, len(perm)), "sk_pool_set_alloc_order")
+        arr = np.ascontiguousarray(perm, dtype=np.int32)
+        _ck(lib().sk_pool_set_alloc_order(self.h, arr.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), arr.size),
+            "sk_pool_set_alloc_order")
 
     def sk_session_create(self):
         out = ctypes.c_int32()

@@ -8,7 +8,7 @@ import torch
 import oracle
 import paper_2605_13784_amd as sk
 from workloads import synth
-from gpu_common import TOL, dev
+from gpu_common import TOL, compare, dev
 
 pytestmark = pytest.mark.gpu
 
@@ -174,3 +174,40 @@ def test_multi_tenant_step_at_full_size():
             ro, rl = refs[i].query(qr[a:b], kr[a:b], vr[a:b], rows=rows)
         _check_rows("item %d (op %d, n=%d)" % (j, ops[j], lengths[i]), out[a:b], lse[a:b], rows, ro, rl, shape.dtype)
         assert pool.sk_session_length(sids[i]) == refs[i].length
+
+
+def test_pool_of_160_gib_serves_a_session_from_its_last_blocks():
+    """Largest pool a test can afford (160 GiB of the 288 GB; nothing in it is initialised beyond what
+    the session writes): the session's blocks are the pool's highest-numbered ones, in a shuffled
+    order, so every byte offset the kernels form is beyond 2^37 for the last KV head.  Ragged
+    appends and both kinds of query against the oracle element by element, cache bit for bit."""
+    shape = synth.CFG2
+    n_blocks = 160 * (1 << 30) // (16 * shape.n_kv_heads * shape.head_dim * 2 * 2)
+    torch.cuda.empty_cache()
+    pool = sk.Pool(shape.dtype, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, 16, n_blocks, max_sessions=2,
+                   max_session_tokens=4096, max_batch_tokens=1024)
+    assert pool.kv_mem.numel() == 160 * (1 << 30)
+    gen = synth.generator(2, stream=40)
+    top = n_blocks - 1 - synth.permutation(gen, 256).astype(np.int64)
+    perm = np.concatenate([top, np.arange(n_blocks - 256, dtype=np.int64)]).astype(np.int32)
+    pool.sk_pool_set_alloc_order(perm)
+    sid = pool.sk_session_create()
+    ref = oracle.OracleSession(shape.dtype, shape.n_q_heads, shape.n_kv_heads, shape.head_dim)
+    for L in (300, 1, 411, 200):
+        q, k, v = synth.draw_qkv(gen, L, shape)
+        out, lse = pool.sk_session_append(sid, dev(q), dev(k), dev(v))
+        ro, rl = ref.append(synth.to_raw(q), synth.to_raw(k), synth.to_raw(v))
+        compare("append %d" % L, out, lse, ro, rl, shape.dtype)
+    table = pool.sk_session_block_table(sid)
+    assert min(table) >= n_blocks - 256 and table != sorted(table)
+    qq, kq, vq = synth.draw_qkv(gen, 24, shape)
+    out, lse = pool.sk_session_query(sid, dev(qq))
+    compare("query A", out, lse, *ref.query(synth.to_raw(qq)), shape.dtype)
+    out, lse = pool.sk_session_query(sid, dev(qq), dev(kq), dev(vq))
+    compare("query B", out, lse, *ref.query(synth.to_raw(qq), synth.to_raw(kq), synth.to_raw(vq)), shape.dtype)
+    kc, vc = pool.sk_session_gather(sid)
+    torch.cuda.synchronize()
+    Kc, Vc = ref.cache()
+    assert np.array_equal(synth.to_raw(kc.cpu()), Kc) and np.array_equal(synth.to_raw(vc.cpu()), Vc)
+    del pool
+    torch.cuda.empty_cache()
