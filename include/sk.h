@@ -102,7 +102,13 @@ size_t sk_pool_kv_bytes(const sk_pool_desc* desc);
 size_t sk_pool_workspace_bytes(const sk_pool_desc* desc);
 
 /* Creates host metadata (and, unless metadata-only, a pinned staging ring on the current
- * device; zeroes nothing in kv_mem).  *out is NULL on error. */
+ * device; zeroes nothing in kv_mem).  *out is NULL on error.
+ * Tuning switches, read from the environment here and fixed for the life of the pool (none
+ * changes a result beyond the rounding order of the split merge; they exist for sweeps):
+ *   SK_TARGET_WGS=n    workgroups a single-session call is cut into (default: 256 or 512 by shape)
+ *   SK_FORCE_SIMPLE=1  always the fp32-FMA attention kernel
+ *   SK_NO_256=1        never the 256-row eight-wave instance of the bf16 kernel
+ *   SK_NO_PACK=1       a question batch gives every question a row tile of its own */
 int sk_pool_create(const sk_pool_desc* desc, sk_pool** out);
 /* Frees host metadata and the staging ring; caller memory is untouched.  The caller must
  * have synchronised the stream(s) the pool was used on. */

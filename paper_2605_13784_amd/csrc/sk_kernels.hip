@@ -246,12 +246,6 @@ __device__ __forceinline__ void sk_issue_tile(const sk_seg& g, int t0, int last_
     sk_issue_group<US, 1>(g, t0, last_group, tb.blk[1], unit_addr, koff, voff);
 }
 
-#ifdef SK_EXPERIMENT              // development builds: P.pad bit 0 = no arithmetic, bit 1 = no loads
-#define SK_EXP_LOADS if (!(P.pad & 2))
-#else
-#define SK_EXP_LOADS
-#endif
-
 template <int NRG, int NPH, int NSS>
 __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_attn_bf16_d128(const sk_launch P)
 {
@@ -260,6 +254,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
     constexpr int TPW = TPI / NPH;           // tiles per wave per iteration
     static_assert(NW == 4 || (NW == 8 && NPH == 1 && NSS == 4), "four waves, or eight in two alternating groups");
     static_assert(NSS == 2 || NSS == 4, "ring depth in iterations: 64 KiB (two workgroups per CU) or 128 KiB (one)");
+    static_assert(NSS * TPI >= NW, "the epilogue transposes one 16 KiB tile per wave in the ring");
     // The ring holds NSS iterations of TPI tiles.  Its 1 KiB units are interleaved: unit u of tile t
     // of ring slot s sits at (u * TPI * NSS + t * NSS + s) KiB, so that from a lane's per-unit base
     // address every tile of the ring is within reach of the 16-bit offset field of an LDS read.
@@ -270,9 +265,6 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
     sk_work w;
     if (!sk_decode_work(P, blockIdx.x, w)) return;
 
-#ifdef SK_EXPERIMENT
-    if (P.pad & 4) return;                     // launch overhead only
-#endif
     const unsigned lds_base = (unsigned)(uintptr_t)(sk_lds_ptr)lds;   // LDS byte address of the ring
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // in a scalar register
@@ -372,11 +364,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
         // first key position of the wave's tiles of iteration `it`, and whether it has work there
         auto first_pos = [&](const int it) __attribute__((always_inline)) { return g.begin + (it * TPI + ph * TPW) * SK_TILE + g.pos_shift; };
         auto is_active = [&](const int it) __attribute__((always_inline)) {
-            bool a = wave_has_rows && it * TPI + ph * TPW < ntiles && first_pos(it) <= lim_wave_max;
-#ifdef SK_EXPERIMENT
-            if (P.pad & 1) a = false;           // stream only: no arithmetic
-#endif
-            return a;
+            return wave_has_rows && it * TPI + ph * TPW < ntiles && first_pos(it) <= lim_wave_max;
         };
 
         // S^T = K Q^T, TPW independent accumulator chains
@@ -486,7 +474,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
                     for (int p = 0; p < TPI; ++p) {
                         const int t0 = g.begin + (a * TPI + p) * SK_TILE;
                         const sk_tile_blocks tb = sk_lookup_tile(g, t0, last_group);
-                        SK_EXP_LOADS sk_issue_tile<US>(g, t0, last_group, tb, unit_base + SK_SLOT_OFF(a, p), koff, voff);
+                        sk_issue_tile<US>(g, t0, last_group, tb, unit_base + SK_SLOT_OFF(a, p), koff, voff);
                     }
                 }
             }
@@ -510,7 +498,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
                 if (it + NSS - 1 < niter) {
 #pragma unroll
                     for (int p = 0; p < TPI; ++p)
-                        SK_EXP_LOADS sk_issue_tile<US>(g, g.begin + ((it + NSS - 1) * TPI + p) * SK_TILE, last_group, nb[p],
+                        sk_issue_tile<US>(g, g.begin + ((it + NSS - 1) * TPI + p) * SK_TILE, last_group, nb[p],
                                                        unit_base + SK_SLOT_OFF((STAGE + NSS - 1) % NSS, p), koff, voff);
                     if (it + NSS < niter) {
 #pragma unroll
@@ -561,7 +549,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
                 if (a < ahead && a < niter) {
                     const int t0 = g.begin + (a * TPI + my_tile) * SK_TILE;
                     const sk_tile_blocks tb = sk_lookup_tile(g, t0, last_group);
-                    SK_EXP_LOADS sk_issue_tile<US>(g, t0, last_group, tb, unit_base + SK_SLOT_OFF(a, my_tile), koff, voff);
+                    sk_issue_tile<US>(g, t0, last_group, tb, unit_base + SK_SLOT_OFF(a, my_tile), koff, voff);
                 }
             }
             sk_tile_blocks nb = sk_lookup_tile(g, g.begin + (ahead * TPI + my_tile) * SK_TILE, last_group);
@@ -577,7 +565,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
             auto refill = [&](const int j) __attribute__((always_inline)) {
                 const int i = j + ahead;
                 if (i < niter) {
-                    SK_EXP_LOADS sk_issue_tile<US>(g, g.begin + (i * TPI + my_tile) * SK_TILE, last_group, nb,
+                    sk_issue_tile<US>(g, g.begin + (i * TPI + my_tile) * SK_TILE, last_group, nb,
                                                    unit_base + SK_SLOT_OFF(i & 3, my_tile), koff, voff);
                     if (i + 1 < niter) nb = sk_lookup_tile(g, g.begin + ((i + 1) * TPI + my_tile) * SK_TILE, last_group);
                 }
@@ -591,9 +579,6 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
             auto matrix_slot = [&](auto kind_const, const int j, const sk_lds_cptr (&kc)[8], const sk_lds_cptr (&vp)[4])
                                    __attribute__((always_inline)) {
                 constexpr int KIND = decltype(kind_const)::value;
-#ifdef SK_EXPERIMENT
-                if (P.pad & 1) return;              // stream only: no arithmetic
-#endif
                 auto ld_v = [&](sk_u32x4 (&o)[4], const int t, const int q) __attribute__((always_inline)) {
 #pragma unroll
                     for (int mt = 0; mt < 4; ++mt) o[mt] = *(sk_lds_u4ptr)(vp[mt] + SK_SLOT_OFF(0, t) + q * 4 * US);
@@ -643,9 +628,6 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
             // Vector slot: softmax of iteration j, and the operands of the first group of matrix
             // instructions of the slot that follows (V^T, first 16 keys of the iteration).
             auto vector_slot = [&](const int j, const sk_lds_cptr (&vc)[4]) __attribute__((always_inline)) {
-#ifdef SK_EXPERIMENT
-                if (P.pad & 1) return;
-#endif
 #pragma unroll
                 for (int mt = 0; mt < 4; ++mt) va0[mt] = *(sk_lds_u4ptr)(vc[mt]);
                 step_softmax(j);
@@ -717,16 +699,13 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
     // ---- epilogue: rows go out through LDS so that every store instruction writes whole rows ----
     // A lane holds 4-float pieces of ONE row (its accumulators are O^T); written as they are, a store
     // instruction would touch 64 different 128-byte lines.  Each wave transposes its 32 x 128 tile in
-    // 16 KiB of the (now idle) ring, XOR-swizzled by row so both directions are conflict-free.  The
-    // ring holds four such tiles: with eight waves, waves 0-3 go first and waves 4-7 after them.
+    // 16 KiB of the (now idle) ring, XOR-swizzled by row so both directions are conflict-free (the
+    // ring holds one such tile per wave: 64 KiB for four waves, 128 KiB for eight).
     if (NPH == 1) __syncthreads();                    // every wave is done reading key tiles
-#ifdef SK_EXPERIMENT
-    if (P.pad & 8) return;                     // no output
-#endif
     const bool direct = w.part < 0;
     auto emit = [&]() __attribute__((always_inline)) {
         const float inv = direct ? 1.0f / l_tot : 1.0f;
-        float* tr = (float*)lds + (NPH == 1 ? (wave & 3) : rg * 2) * 4096;
+        float* tr = (float*)lds + (NPH == 1 ? wave : rg * 2) * 4096;
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
@@ -761,12 +740,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
             }
         }
     };
-    if (NW == 4) emit();
-    else {
-        if (wave < 4) emit();
-        __syncthreads();
-        if (wave >= 4) emit();
-    }
+    emit();
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -111,8 +111,10 @@ struct sk_pool {
     sk_geom geom;
     sk_pool_stats stats = {};
     sk_launch_info last = {};
+    // Tuning switches, read from the environment once when the pool is created (see sk_pool_create).
     int target_wgs = kDefaultTargetWgs;
-    bool target_wgs_set = false;         // overridden through the environment (tuning sweeps)
+    bool target_wgs_set = false;
+    bool force_simple = false, no_256 = false, no_pack = false;
     // optional kernel timing
     bool profiling = false;
     std::vector<hipEvent_t> prof_ev;     // triples: before attention, after attention, after combine
@@ -186,8 +188,7 @@ bool pick_variant(const sk_pool* p, int64_t n_tok, Variant& v, bool allow_256 = 
 {
     const int G = p->L.G;
     const bool mfma_ok = p->d.dtype == SK_BF16 && p->d.head_dim == 128 && ilog2_exact(G) >= 0 && G <= 32;
-    const char* force_simple = getenv("SK_FORCE_SIMPLE");
-    if (mfma_ok && !(force_simple && force_simple[0] == '1')) {
+    if (mfma_ok && !p->force_simple) {
         if (allow_256 && n_tok * G > 128) { v.id = SK_KV_MFMA256; v.rows_per_slot = 256; v.tok_per_tile = 256 / G; }
         else if (n_tok * G > 64) { v.id = SK_KV_MFMA128; v.rows_per_slot = 128; v.tok_per_tile = 128 / G; }
         else { v.id = SK_KV_MFMA64; v.rows_per_slot = 64; v.tok_per_tile = 64 / G; }
@@ -217,8 +218,7 @@ int run_regular(sk_pool* p, int32_t id, const void* q, int64_t n_tok, int32_t po
                 int32_t n_splits_req, hipStream_t st)
 {
     Variant v;
-    const char* no256 = getenv("SK_NO_256");
-    if (!pick_variant(p, n_tok, v, !(no256 && no256[0] == '1'))) return SK_E_SHAPE;
+    if (!pick_variant(p, n_tok, v, !p->no_256)) return SK_E_SHAPE;
     sk_launch L;
     fill_launch_common(p, L, q, out, out_dtype, lse, v);
     L.mode = SK_MODE_REGULAR;
@@ -257,9 +257,6 @@ int run_regular(sk_pool* p, int32_t id, const void* q, int64_t n_tok, int32_t po
     L.n_splits = (int32_t)parts;
     L.eph_blk[0] = 0; L.eph_cnt[0] = eph_cnt; L.eph_pos0[0] = eph_pos0;
     L.hole_lo = (int32_t)p->sessions[id].frozen; L.hole_hi = (int32_t)p->sessions[id].win;
-#ifdef SK_EXPERIMENT
-    if (const char* x = getenv("SK_EXPERIMENT")) L.pad = atoi(x);
-#endif
     const int32_t wgs = int32_t(base_wgs * parts);
     hipEvent_t* pe = prof_begin(p, st);
     int e = sk_launch_attention(L, v.id, wgs, st);
@@ -609,6 +606,10 @@ int sk_pool_create(const sk_pool_desc* desc, sk_pool** out)
     g.d = desc->head_dim; g.elem = L.elem;
     g.scale_log2e = scale * 1.4426950408889634f;
     if (const char* t = getenv("SK_TARGET_WGS")) { int x = atoi(t); if (x > 0) { p->target_wgs = x; p->target_wgs_set = true; } }
+    auto env_on = [](const char* name) { const char* x = getenv(name); return x && x[0] == '1'; };
+    p->force_simple = env_on("SK_FORCE_SIMPLE");
+    p->no_256 = env_on("SK_NO_256");
+    p->no_pack = env_on("SK_NO_PACK");
     if (!meta_only) {
         hipError_t e = hipHostMalloc((void**)&p->ring, kMetaBytes * kRingSlots, hipHostMallocDefault);
         if (e != hipSuccess) { g_last_hip = (int)e; delete p; return SK_E_HIP; }
@@ -806,8 +807,7 @@ int sk_batch_step(sk_pool* p, int32_t n_items, const int32_t* session_id, const 
     ScatterBatch sb;
     sb.k = k; sb.v = v;
     ListGroup groups[3];
-    const char* no256 = getenv("SK_NO_256");
-    const bool allow_256 = !(no256 && no256[0] == '1');
+    const bool allow_256 = !p->no_256;
     int64_t eph_cursor = 0;
     for (int i = 0; i < n_items; ++i) {
         Session* s = get_session(p, session_id[i]);
@@ -898,9 +898,8 @@ int sk_session_query_shared_prefix(sk_pool* p, int32_t id, const void* qp, const
         // kernel (their rows see the same cache and prefix; each sees its own suffix), when a
         // question's rows are a multiple of a wave's 32 and divide 256.
         const int64_t rows_q = int64_t(Sfx) * p->L.G;
-        const char* no_pack = getenv("SK_NO_PACK");
         const bool pack = groups[1].v.id != SK_KV_SIMPLE && rows_q < 256 && rows_q % 32 == 0 && 256 % rows_q == 0 && NQ > 1 &&
-                          !(no_pack && no_pack[0] == '1');
+                          !p->no_pack;
         const int32_t per_tile = pack ? int32_t(256 / rows_q) : 1;
         if (pack) groups[1].v = Variant{SK_KV_MFMA256, 256, 256 / p->L.G};
         for (int32_t j = 0; j < NQ; ++j)
