@@ -722,7 +722,10 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
         const int c4 = lane & 31;
 #pragma unroll
         for (int it = 0; it < 16; ++it) {
-            const int row = it * 2 + (lane >> 5);
+            // the row order is rotated by the workgroup index: workgroups that finish together (short
+            // contexts) would otherwise all write the same offset of their partial slots, which lie a
+            // power of two apart, at the same time, and crowd onto a few memory channels
+            const int row = ((it + blockIdx.x) & 15) * 2 + (lane >> 5);
             const float4 val = *(const float4*)(tr + row * 128 + ((c4 ^ row) & 31) * 4);
             const int rit = rg * 32 + row;                 // row inside the tile
             const int tok2 = rit >> log2G;
