@@ -220,13 +220,17 @@ def stream_workload(sk, name, args, steps, warmup, calibrate=False):
     a_kernel_us = float(app_attn.mean() * 1e3)
     a_total_us = float((app_attn + app_comb).mean() * 1e3)
     traffic = MEASURED_HBM_TRAFFIC.get((name, B, "cold" if not args.hot else "hot"), {})
+    def hbm(kind):      # "traffic" = measured HBM bytes per launch (fetch + write), null when not measured
+        t = traffic.get(kind)
+        return {"traffic": None} if t is None else {"traffic": t["total_bytes"], "traffic_fetch_bytes": t["fetch_bytes"],
+                                                    "traffic_write_bytes": t["write_bytes"]}
     roof_q = {"kernel": "sk_attn_bf16_d128 (query, split-KV partial)", "bound": "hbm",
               "achieved": qb / (q_kernel_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-              "frac": qb / (q_kernel_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, "traffic": traffic.get("query"),
+              "frac": qb / (q_kernel_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, **hbm("query"),
               "avg_kernel_us": q_kernel_us, "algorithmic_bytes": qb}
     roof_a = {"kernel": "sk_attn_bf16_d128 (append, causal over cache + chunk)", "bound": "mfma",
               "achieved": af / (a_kernel_us * 1e-6) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-              "frac": af / (a_kernel_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic.get("append"),
+              "frac": af / (a_kernel_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, **hbm("append"),
               "avg_kernel_us": a_kernel_us, "algorithmic_flops": af}
     return {
         "tokens_per_s": (L + nq) * steps / wall, "ms_per_step": wall * 1e3 / steps,
