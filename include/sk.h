@@ -219,7 +219,10 @@ int sk_session_evict_oldest(sk_pool* pool, int32_t id, int64_t n_tokens, void* h
  * inside a block does the new session get a copy of that one block, into which its own appends
  * then go.  Cost: n_prefix / block_tokens table entries and at most one block of K/V, whatever the
  * prefix length.  Afterwards the two sessions are independent: appends, evictions, truncations
- * and destruction of one never change what the other reads.
+ * and destruction of one never change what the other reads.  A shared block is never written:
+ * when a truncation has left a session's end inside one, that session's next append first
+ * replaces the block by a copy of its own (one more free block needed, part of the append's
+ * all-or-nothing check; the copy is ordered on the append's stream).
  * The device work (table upload, block copy) is ordered on hip_stream, which must be the stream
  * of src's earlier calls.  SK_E_NOMEM when no session id or (if needed) no block is free.
  */

@@ -349,6 +349,33 @@ void release_block(sk_pool* p, int32_t b)
     if (--p->refcnt[(size_t)b] == 0) { p->free_blocks.push_back(b); p->blocks_in_use--; }
 }
 
+// After a fork, a truncation can leave the end of a session inside a block that other sessions
+// also hold.  Before such a session appends it gets its own copy of that block: the one case of
+// copy-on-write (nothing else ever writes into a block that is not the writer's alone).
+bool tail_shared(const sk_pool* p, const Session* s)
+{
+    return s->len % p->d.block_tokens != 0 && p->refcnt[(size_t)s->blocks.back()] > 1;
+}
+
+// The caller has checked that a block is free.  The copy is ordered on `st` in front of the
+// scatter that follows; the scatter also rewrites the table entry (it is told that the block is new).
+int unshare_tail(sk_pool* p, Session* s, hipStream_t st)
+{
+    const int32_t old = s->blocks.back();
+    const int32_t blk = p->free_blocks.front();
+    p->free_blocks.pop_front();
+    p->refcnt[(size_t)blk] = 1;
+    p->refcnt[(size_t)old]--;                 // still held by the others
+    p->blocks_in_use++;
+    s->blocks.back() = blk;
+    if (!p->device) return SK_OK;
+    unsigned char* kv = (unsigned char*)p->d.kv_mem;
+    SK_HIP(hipMemcpy2DAsync(kv + int64_t(blk) * p->L.blk_stride, (size_t)p->L.head_stride,
+                            kv + int64_t(old) * p->L.blk_stride, (size_t)p->L.head_stride,
+                            (size_t)p->L.blk_stride, (size_t)p->d.n_kv_heads, hipMemcpyDeviceToDevice, st));
+    return SK_OK;
+}
+
 int check_out_dtype(const sk_pool* p, int out_dtype)
 {
     if (out_dtype != SK_F32 && out_dtype != p->d.dtype) return SK_E_DTYPE;
@@ -719,15 +746,17 @@ int sk_session_append(sk_pool* p, int32_t id, const void* q, const void* k, cons
     }
     if (s->len + L > p->L.max_session_tokens) return SK_E_NOMEM;
     const int64_t need = blocks_needed(p, s->len, L);
-    if (need > (int64_t)p->free_blocks.size()) return SK_E_NOMEM;
+    const bool unshare = tail_shared(p, s);
+    if (need + (unshare ? 1 : 0) > (int64_t)p->free_blocks.size()) return SK_E_NOMEM;
     // from here on nothing can fail for lack of resources
-    const int64_t first_new = (int64_t)s->blocks.size();
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (unshare) { int rc = unshare_tail(p, s, st); if (rc) return rc; }
+    const int64_t first_new = (int64_t)s->blocks.size() - (unshare ? 1 : 0);
     const int64_t n = s->len;
     take_blocks(p, s, need);
     s->len = n + L;
     p->stats.tokens_appended += L;
     if (!p->device) return SK_OK;
-    hipStream_t st = (hipStream_t)hip_stream;
     std::vector<sk_scatter> items;
     build_scatter(p, s, id, n, 0, L, first_new, false, 0, items);
     int rc = upload_and_scatter(p, items, k, v, st);
@@ -787,7 +816,7 @@ int sk_batch_step(sk_pool* p, int32_t n_items, const int32_t* session_id, const 
         if (T == 0) continue;
         if (op[i] == SK_OP_APPEND) {
             if (s->len + T > p->L.max_session_tokens) return SK_E_NOMEM;
-            need_blocks += blocks_needed(p, s->len, T);
+            need_blocks += blocks_needed(p, s->len, T) + (tail_shared(p, s) ? 1 : 0);
         }
         if (op[i] == SK_OP_QUERY_A && s->retained() == 0) return SK_E_EMPTY;
         if (op[i] != SK_OP_QUERY_A) any_kv = true;
@@ -820,7 +849,9 @@ int sk_batch_step(sk_pool* p, int32_t n_items, const int32_t* session_id, const 
         base.tbl_off = tbl_off;
         base.hole_lo = (int32_t)s->frozen; base.hole_hi = (int32_t)s->win;
         if (op[i] == SK_OP_APPEND) {
-            const int64_t first_new = (int64_t)s->blocks.size();
+            const bool unshare = tail_shared(p, s);
+            if (unshare) { int rc = unshare_tail(p, s, (hipStream_t)hip_stream); if (rc) return rc; }
+            const int64_t first_new = (int64_t)s->blocks.size() - (unshare ? 1 : 0);
             take_blocks(p, s, blocks_needed(p, n, T));
             s->len = n + T;
             p->stats.tokens_appended += T;

@@ -138,3 +138,37 @@ def test_fork_then_diverge(n_prefix):
     q, k, v = synth.draw_qkv(gen, 64, shape)
     pr.append(b, q, k, v, name="append to the fork after the source is gone")
     pr.check_cache(b)
+
+
+@pytest.mark.parametrize("block_tokens", [16, 64])
+def test_truncate_into_a_shared_block_then_append(block_tokens):
+    """SeqRemove on one holder of a shared prefix, then new tokens: the session whose end lies inside
+    a block that the other still reads gets its own copy of the block before it writes (single-session
+    append and batched step), so neither session ever sees the other's tokens."""
+    shape = synth.CFG2
+    gen = synth.generator(2, stream=70 + block_tokens)
+    pr = Pair(shape, block_tokens=block_tokens, n_blocks=200, kv_fill=0xFF, max_sessions=3, max_batch_tokens=2048)
+    a = pr.create()
+    q, k, v = synth.draw_qkv(gen, 512, shape)
+    pr.append(a, q, k, v, check=False)
+    b = pr.pool.sk_session_fork(a, 512)                    # block-aligned: every block shared, nothing copied
+    pr.oracles[b] = pr.oracles[a].fork(512)
+    assert pr.pool.sk_session_block_table(b) == pr.pool.sk_session_block_table(a)
+    pr.pool.sk_session_truncate(a, 300); pr.oracles[a].truncate(300)       # a ends inside a block b reads
+    q, k, v = synth.draw_qkv(gen, 150, shape)
+    pr.append(a, q, k, v, name="source appends after truncating into a shared block")
+    pr.check_cache(a); pr.check_cache(b)
+    qq, kq, vq = synth.draw_qkv(gen, 24, shape)
+    pr.query(b, qq, name="fork still reads its own tokens")
+    pr.query(a, qq, kq, vq, name="source reads its new tokens")
+    # the fork's turn, through the batched call
+    pr.pool.sk_session_truncate(b, 77); pr.oracles[b].truncate(77)
+    cu = np.array([0, 40, 56], dtype=np.int32)
+    q, k, v = synth.draw_qkv(gen, 56, shape)
+    out, lse = pr.pool.sk_batch_step([b, a], [sk.SK_OP_APPEND, sk.SK_OP_QUERY_A], cu, dev(q), dev(k), dev(v))
+    ro0, rl0 = pr.oracles[b].append(synth.to_raw(q[:40]), synth.to_raw(k[:40]), synth.to_raw(v[:40]))
+    ro1, rl1 = pr.oracles[a].query(synth.to_raw(q[40:]))
+    compare("batched append into a shared block", out, lse, np.concatenate([ro0, ro1]), np.concatenate([rl0, rl1]), shape.dtype)
+    pr.check_cache(a); pr.check_cache(b)
+    pr.pool.sk_session_destroy(a); pr.pool.sk_session_destroy(b)
+    assert pr.pool.sk_pool_blocks_free() == 200

@@ -239,3 +239,39 @@ def test_fork_shares_blocks_by_reference_count():
     e2 = p.sk_session_fork(a, 0)
     assert p.sk_session_length(e2) == 0 and p.sk_session_block_table(e2) == []
     assert p.sk_pool_get_stats()["forks"] == 4
+
+
+def test_append_into_a_shared_block_takes_a_copy_first():
+    """After a fork, a truncation can leave a session's end inside a block that another session still
+    reads.  The next append must not write there: the session swaps that block for a fresh one (one
+    extra block, counted in the all-or-nothing check), the other holder keeps the old one."""
+    p = meta_pool(n_blocks=8, block_tokens=16, max_sessions=3)
+    a = p.sk_session_create()
+    p.reserve(a, 64)                                     # blocks 0..3, all full
+    b = p.sk_session_fork(a, 64)                         # all four shared
+    assert p.sk_session_block_table(b) == [0, 1, 2, 3] and p.sk_pool_blocks_free() == 4
+    p.sk_session_truncate(a, 40)                         # a ends inside block 2, which b still reads
+    assert p.sk_session_block_table(a) == [0, 1, 2] and p.sk_pool_blocks_free() == 4
+    p.reserve(a, 4)                                      # stays inside the block: still needs the copy
+    assert p.sk_session_block_table(a) == [0, 1, 4] and p.sk_session_block_table(b) == [0, 1, 2, 3]
+    assert p.sk_pool_blocks_free() == 3
+    p.reserve(a, 4)                                      # the block is a's alone now: nothing more to take
+    assert p.sk_session_block_table(a) == [0, 1, 4] and p.sk_pool_blocks_free() == 3
+    # the fork side: b truncates into block 1 (shared with a) and grows past it
+    p.sk_session_truncate(b, 20)                         # b lets go of 2 and 3 (nobody else holds them now)
+    assert p.sk_pool_blocks_free() == 5
+    p.reserve(b, 30)                                     # copy of block 1 + two more blocks
+    tb = p.sk_session_block_table(b)
+    assert tb[0] == 0 and tb[1] not in (1, 4) and len(tb) == 4 and p.sk_pool_blocks_free() == 2
+    assert p.sk_session_block_table(a) == [0, 1, 4]
+    # all-or-nothing: the copy counts
+    c = p.sk_session_fork(a, 32)                         # shares 0 and 1 with a
+    p.sk_session_truncate(c, 17)
+    p.reserve(a, 16 * 2 - 8)                             # a fills its last block and takes the two free ones
+    assert p.sk_pool_blocks_free() == 0
+    with pytest.raises(sk.SkError) as e:
+        p.reserve(c, 1)                                  # would need a copy of block 1: no block left
+    assert e.value.status == sk.SK_E_NOMEM and p.sk_session_length(c) == 17 and p.sk_session_block_table(c) == [0, 1]
+    for s in (a, b, c):
+        p.sk_session_destroy(s)
+    assert p.sk_pool_blocks_free() == 8
