@@ -6,6 +6,7 @@
 #include "sk_internal.h"
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 #define SK_NEG_INF (-__builtin_inff())
@@ -442,10 +443,25 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
 #pragma unroll
                 for (int v = 0; v < 8; ++v) {
                     const float p0 = sk_exp2(fmaf(sacc[t][v], c_scale, neg_m)), p1 = sk_exp2(fmaf(sacc[t][8 + v], c_scale, neg_m));
-                    l_run += p0 + p1;
                     pb[t][0][v] = (__bf16)p0;
                     pb[t][1][v] = (__bf16)p1;
                 }
+            // The row sum is taken over the weights as the matrix pipe sees them (rounded to bf16), two
+            // per instruction with fp32 accumulation: numerator and denominator of the output then
+            // carry the same weights, so a row that one key dominates keeps that key's value to fp32
+            // accuracy whatever the rounding of its weight (with the lazy maximum that weight is not 1).
+            const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+            float ls0 = 0.f, ls1 = 0.f;
+#pragma unroll
+            for (int t = 0; t < TPW; ++t)
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    ls0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pb[t][q], pb[t][q], 0, 1), ones, ls0, false);
+                    ls1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pb[t][q], pb[t][q], 2, 3), ones, ls1, false);
+                    ls0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pb[t][q], pb[t][q], 4, 5), ones, ls0, false);
+                    ls1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pb[t][q], pb[t][q], 6, 7), ones, ls1, false);
+                }
+            l_run += ls0 + ls1;
         };
         // O^T += V^T P^T for one tile
         auto pv_tile = [&](const int t) __attribute__((always_inline)) {
