@@ -18,11 +18,14 @@ MAX_LEN = 2600          # a session that grows beyond this is cut back (evict or
 
 
 class Walk:
-    def __init__(self, shape, block_tokens, max_sessions, seed):
+    def __init__(self, shape, block_tokens, max_sessions, seed, tight=False):
         self.shape, self.B = shape, block_tokens
         self.rng = np.random.default_rng(seed)
         self.gen = synth.generator(6, stream=seed)
         n_blocks = max_sessions * ((MAX_LEN + 1400) // block_tokens + 3)
+        if tight:               # a pool that runs out: refused calls must change nothing
+            n_blocks = max(8, (MAX_LEN + 600) // block_tokens)
+        self.refused = 0
         self.pool = sk.Pool(shape.dtype, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, block_tokens, n_blocks,
                             max_sessions=max_sessions, max_batch_tokens=2048, kv_fill=0xFF)
         self.pool.sk_pool_set_alloc_order(synth.permutation(self.gen, n_blocks))
@@ -72,11 +75,24 @@ class Walk:
         sid = self.pick()
         L = int(self.rng.choice([1, 7, 16, 33, 64, 100, 129, 256, 300]))
         q, k, v = self.draw(L)
-        name = "append %d tokens to session %d at %d" % (L, sid, self.ref[sid].length)
-        out, lse = self.pool.sk_session_append(sid, dev(q), dev(k), dev(v))
+        odt = "bf16" if self.shape.dtype == "bf16" and self.rng.integers(4) == 0 else "f32"
+        name = "append %d tokens to session %d at %d, out %s" % (L, sid, self.ref[sid].length, odt)
+        try:
+            out, lse = self.pool.sk_session_append(sid, dev(q), dev(k), dev(v), out_dtype=odt)
+        except sk.SkError as e:
+            return self.was_refused(e, name)
         ro, rl = self.ref[sid].append(synth.to_raw(q), synth.to_raw(k), synth.to_raw(v))
-        compare(name, out, lse, ro, rl, self.shape.dtype)
+        compare(name, out, lse, ro, rl, self.shape.dtype, odt == "bf16")
         return name
+
+    def was_refused(self, e, name):
+        """The pool is out of blocks: the call must have changed nothing (checked by every later
+        comparison and cache read-back, since the oracle was not told about it)."""
+        assert e.status == sk.SK_E_NOMEM, name
+        self.refused += 1
+        for sid in sorted(self.ref):
+            assert self.pool.sk_session_length(sid) == self.ref[sid].length, name
+        return name + " (refused: no blocks)"
 
     def op_query(self):
         mode_b = bool(self.rng.integers(2))
@@ -87,13 +103,17 @@ class Walk:
         q, k, v = self.draw(nq)
         kw = {"n_splits": int(self.rng.choice([0, 0, 1, 2, 5]))}
         name = "query %s, %d tokens, session %d at %d, n_splits %d" % ("B" if mode_b else "A", nq, sid, self.ref[sid].length, kw["n_splits"])
+        if self.shape.dtype == "bf16" and self.rng.integers(4) == 0:
+            kw["out_dtype"] = "bf16"
+        if self.rng.integers(5) == 0:
+            kw["want_lse"] = False
         if mode_b:
             out, lse = self.pool.sk_session_query(sid, dev(q), dev(k), dev(v), **kw)
             ro, rl = self.ref[sid].query(synth.to_raw(q), synth.to_raw(k), synth.to_raw(v))
         else:
             out, lse = self.pool.sk_session_query(sid, dev(q), **kw)
             ro, rl = self.ref[sid].query(synth.to_raw(q))
-        compare(name, out, lse, ro, rl, self.shape.dtype)
+        compare(name + " %s" % sorted(kw.items()), out, lse, ro, rl, self.shape.dtype, kw.get("out_dtype") == "bf16")
         return name
 
     def op_batch(self):
@@ -112,7 +132,10 @@ class Walk:
             return None
         q, k, v = self.draw(T)
         name = "batch step sessions %s ops %s counts %s" % (ids, ops, counts)
-        out, lse = self.pool.sk_batch_step(ids, ops, cu, dev(q), dev(k), dev(v))
+        try:
+            out, lse = self.pool.sk_batch_step(ids, ops, cu, dev(q), dev(k), dev(v))
+        except sk.SkError as e:
+            return self.was_refused(e, name)
         qr, kr, vr = synth.to_raw(q), synth.to_raw(k), synth.to_raw(v)
         ro = np.zeros((T, self.shape.n_q_heads, self.shape.head_dim)); rl = np.zeros((T, self.shape.n_q_heads))
         for i, (s, op) in enumerate(zip(ids, ops)):
@@ -188,7 +211,10 @@ class Walk:
         src = self.pick()
         o = self.ref[src]
         n = int(self.rng.integers(0, o.length + 1)) if self.rng.integers(3) else o.length
-        new = self.pool.sk_session_fork(src, n)
+        try:
+            new = self.pool.sk_session_fork(src, n)
+        except sk.SkError as e:
+            return self.was_refused(e, "fork session %d at %d" % (src, n))
         assert new not in self.ref
         self.ref[new] = o.fork(n)
         self.may_freeze[new] = self.may_freeze[src] or n <= o.n_frozen
@@ -232,6 +258,7 @@ class Walk:
             owned.update(self.pool.sk_session_block_table(sid))
         assert self.pool.sk_pool_blocks_free() == self.pool.desc.n_blocks - len(owned)
         assert all(self.count.get(f.__name__, 0) > 0 for f, _ in table), self.count      # the walk reached every operation
+        return self.refused
 
 
 @pytest.mark.parametrize("shape,block_tokens,max_sessions,seed,n_ops", [
@@ -246,3 +273,14 @@ class Walk:
 ])
 def test_random_walk_over_the_session_api(shape, block_tokens, max_sessions, seed, n_ops):
     Walk(shape, block_tokens, max_sessions, seed).run(n_ops)
+
+
+@pytest.mark.parametrize("shape,block_tokens,max_sessions,seed,n_ops", [
+    (synth.Shape("bf16", 8, 2, 128), 16, 5, 201, 400),
+    (synth.CFG1, 64, 4, 202, 300),
+])
+def test_random_walk_in_a_pool_that_runs_out_of_blocks(shape, block_tokens, max_sessions, seed, n_ops):
+    """Same walk with blocks for about one long session in all: appends, batch steps and forks are
+    refused now and then (all or nothing), and everything keeps agreeing with the oracle, which never
+    hears of a refused call."""
+    assert Walk(shape, block_tokens, max_sessions, seed, tight=True).run(n_ops) > 0
