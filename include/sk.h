@@ -87,7 +87,7 @@ typedef struct sk_pool_desc {
     int32_t block_tokens;     /* power of two, 16..1024 */
     int32_t max_sessions;     /* >= 1 */
     int64_t n_blocks;         /* blocks in the pool */
-    int64_t max_session_tokens; /* longest session; 0 => n_blocks * block_tokens */
+    int64_t max_session_tokens; /* longest session; 0 => n_blocks * block_tokens; capped at 2^20 blocks */
     int32_t max_batch_tokens; /* most new tokens (appends + queries) in one call; 0 => 4096 */
     int32_t flags;            /* 0 or SK_POOL_METADATA_ONLY (host bookkeeping only: no device
                                  memory, compute calls only do their allocation part; lets a

@@ -71,6 +71,7 @@ bool derive_layout(const sk_pool_desc& d, Layout& L)
     L.eph_head_stride = 0;     // set once the number of staging blocks is known
     int64_t mst = d.max_session_tokens ? d.max_session_tokens : d.n_blocks * d.block_tokens;
     mst = std::min<int64_t>(mst, d.n_blocks * d.block_tokens);
+    mst = std::min<int64_t>(mst, int64_t(kMetaBytes / 4) * d.block_tokens);    // a session's block table is uploaded in one piece
     if (mst > (int64_t(1) << 29)) return false;       // positions are int32 with head room
     L.max_session_tokens = mst;
     L.max_blocks_per_session = (mst + d.block_tokens - 1) / d.block_tokens;
@@ -1029,7 +1030,6 @@ int sk_session_evict_oldest(sk_pool* p, int32_t id, int64_t n_tokens, void* hip_
     int rc = ring_acquire(p, &slot, &host);
     if (rc) return rc;
     const size_t bytes = (s->blocks.size() - (size_t)b0) * sizeof(int32_t);
-    if (bytes > kMetaBytes) return SK_E_WORKSPACE;         // more than a million blocks behind the hole
     memcpy(host, s->blocks.data() + b0, bytes);
     int32_t* dev_tbl = (int32_t*)((unsigned char*)p->d.workspace + p->L.off_tables) + int64_t(id) * p->L.max_blocks_per_session + b0;
     hipStream_t st = (hipStream_t)hip_stream;
@@ -1077,7 +1077,6 @@ int sk_session_fork(sk_pool* p, int32_t src_id, int64_t n_prefix, int32_t* out_i
     int rc = ring_acquire(p, &slot, &host);
     if (rc) return rc;
     const size_t bytes = (size_t)n_blk * sizeof(int32_t);
-    if (bytes > kMetaBytes) return SK_E_WORKSPACE;
     memcpy(host, d.blocks.data(), bytes);
     int32_t* dev_tbl = (int32_t*)((unsigned char*)p->d.workspace + p->L.off_tables) + int64_t(id) * p->L.max_blocks_per_session;
     SK_HIP(hipMemcpyAsync(dev_tbl, host, bytes, hipMemcpyHostToDevice, st));
