@@ -142,3 +142,56 @@ def test_latency_scales_with_bytes_not_with_history():
         st = pr.pool.sk_pool_get_stats()
         assert st["tokens_appended"] == 4000 and st["tokens_queried"] == 32
     assert geos[0] == geos[1]
+
+
+def test_two_pools_on_two_streams():
+    """The library enqueues on the caller's stream and orders its own uploads and copies there: two
+    pools driven alternately on two non-default streams (appends with eviction and a fork on one,
+    batched steps on the other, while the default stream is kept busy) give what the oracle gives."""
+    gen = synth.generator(2, stream=15)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    busy = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    p1 = Pair(SHAPE, n_blocks=300, max_sessions=3, max_batch_tokens=2048)
+    p2 = Pair(SHAPE, block_tokens=64, n_blocks=100, max_sessions=3, max_batch_tokens=2048)
+    a = p1.create()
+    b, c = p2.create(), p2.create()
+    results, keep_alive = [], []          # inputs stay allocated until both streams have drained
+    for rnd in range(4):
+        busy.fill_(rnd)                                        # unrelated work on the default stream
+        q, k, v = _stream(gen, 300)
+        q2, k2, v2 = _stream(gen, 200)
+        qd, kd, vd, q2d, k2d, v2d = (dev(t) for t in (q, k, v, q2, k2, v2))
+        keep_alive.append((qd, kd, vd, q2d, k2d, v2d))
+        s1.wait_stream(torch.cuda.current_stream()); s2.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s1):
+            o1, l1 = p1.pool.sk_session_append(a, qd, kd, vd)
+            if rnd == 1:
+                p1.pool.sk_session_evict_oldest(a, 133)
+            if rnd == 2:
+                f = p1.pool.sk_session_fork(a, 250)
+            oq, lq = p1.pool.sk_session_query(a, qd[:24])
+        with torch.cuda.stream(s2):
+            cu = np.array([0, 150, 200], dtype=np.int32)
+            ops = [sk.SK_OP_APPEND, sk.SK_OP_QUERY_B if rnd % 2 else sk.SK_OP_APPEND]
+            o2, l2 = p2.pool.sk_batch_step([b, c], ops, cu, q2d, k2d, v2d)
+        results.append((rnd, q, k, v, q2, k2, v2, ops, o1, l1, oq, lq, o2, l2))
+    s1.synchronize(); s2.synchronize()
+    for rnd, q, k, v, q2, k2, v2, ops, o1, l1, oq, lq, o2, l2 in results:
+        qr, kr, vr = synth.to_raw(q), synth.to_raw(k), synth.to_raw(v)
+        compare("stream 1 append, round %d" % rnd, o1, l1, *p1.oracles[a].append(qr, kr, vr), SHAPE.dtype)
+        if rnd == 1:
+            p1.oracles[a].evict_oldest(133)
+        if rnd == 2:
+            p1.oracles[f] = p1.oracles[a].fork(250)
+        compare("stream 1 query, round %d" % rnd, oq, lq, *p1.oracles[a].query(qr[:24]), SHAPE.dtype)
+        q2r, k2r, v2r = synth.to_raw(q2), synth.to_raw(k2), synth.to_raw(v2)
+        ro0, rl0 = p2.oracles[b].append(q2r[:150], k2r[:150], v2r[:150])
+        if ops[1] == sk.SK_OP_APPEND:
+            ro1, rl1 = p2.oracles[c].append(q2r[150:], k2r[150:], v2r[150:])
+        else:
+            ro1, rl1 = p2.oracles[c].query(q2r[150:], k2r[150:], v2r[150:])
+        compare("stream 2 batch step, round %d" % rnd, o2, l2, np.concatenate([ro0, ro1]), np.concatenate([rl0, rl1]), SHAPE.dtype)
+    with torch.cuda.stream(s1):
+        p1.check_cache(a); p1.check_cache(f)
+    with torch.cuda.stream(s2):
+        p2.check_cache(b); p2.check_cache(c)
