@@ -113,7 +113,9 @@ size_t sk_pool_workspace_bytes(const sk_pool_desc* desc);
  *   SK_TARGET_WGS=n    workgroups a single-session call is cut into (default: 256 or 512 by shape)
  *   SK_FORCE_SIMPLE=1  always the fp32-FMA attention kernel
  *   SK_NO_256=1        never the 256-row eight-wave instance of the bf16 kernel
- *   SK_NO_PACK=1       a question batch gives every question a row tile of its own */
+ *   SK_NO_PACK=1       a question batch gives every question a row tile of its own
+ *   SK_NO_INTERLEAVE=1 the splits of a query take contiguous chunks of the cache instead of
+ *                      interleaved 64-key pieces */
 int sk_pool_create(const sk_pool_desc* desc, sk_pool** out);
 /* Frees host metadata and the staging ring; caller memory is untouched.  The caller must
  * have synchronised the stream(s) the pool was used on. */

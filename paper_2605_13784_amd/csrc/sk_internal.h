@@ -57,7 +57,8 @@ struct sk_work {
     int32_t hole_hi;      // blocks are still streamed, the keys never attended to; empty when lo == hi
     int32_t tok_period;   // > 0: the tile packs sequences of tok_period tokens each, all starting at pos0;
     int32_t sub_blocks;   // sequence k's second uncommitted segment starts at staging block eph_blk[1] + k * sub_blocks
-    int32_t pad[2];
+    int32_t kv_step;      // keys from one 64-key iteration over [kv_begin, kv_end) to the next; 0 = 64 (contiguous)
+    int32_t pad;
 };
 
 // One row tile of the cross-split combine.
@@ -104,7 +105,10 @@ struct sk_launch {
     int32_t tbl_off, n_tok, tok_per_tile, n_tiles, pos0, kv_len, chunk, n_splits;
     int32_t eph_blk[2], eph_cnt[2], eph_pos0[2];
     int32_t hole_lo, hole_hi;    // evicted cached tokens of the session (regular mode)
-    int32_t pad;
+    // regular mode, no causal limit inside the cached range: split s takes the 64-key pieces s, s + S,
+    // s + 2S, .. of the cache instead of one contiguous chunk, so that the workgroups of a head walk
+    // through memory side by side instead of as S separate streams (the host decides when)
+    int32_t interleave;
 };
 
 // Launchers implemented in sk_kernels.hip (return hipError_t as int).

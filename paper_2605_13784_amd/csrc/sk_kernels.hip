@@ -66,8 +66,13 @@ __device__ __forceinline__ bool sk_decode_work(const sk_launch& P, int b, sk_wor
     bool has_eph = (P.eph_cnt[0] > 0 || P.eph_cnt[1] > 0);
     bool eph_part = has_eph && (split == np - 1);
     w.tbl_off = P.tbl_off; w.kv_head = head; w.q_tok0 = tok0; w.n_tok = ntok; w.pos0 = P.pos0 < SK_NO_CAUSAL ? P.pos0 + tok0 : P.pos0;
+    w.kv_step = 0;
     if (eph_part) { w.kv_begin = 0; w.kv_end = 0; }
-    else {
+    else if (P.interleave) {          // every split's first piece exists: the host keeps splits <= kv_len / 256
+        w.kv_begin = split * 64;
+        w.kv_end = kv_vis;
+        w.kv_step = (np - (has_eph ? 1 : 0)) * 64;
+    } else {
         w.kv_begin = split * P.chunk;
         int e = w.kv_begin + P.chunk;
         w.kv_end = e < kv_vis ? e : kv_vis;
@@ -90,6 +95,7 @@ struct sk_seg {
     int64_t blk_stride;
     int32_t v_off, B, log2B;
     int32_t begin, end;          // token indices; begin is a multiple of 16
+    int32_t step;                // iteration i covers the 64 keys from begin + i * step (64: one contiguous run)
     int32_t pos_shift;           // absolute position = token index + pos_shift
     int32_t hole_lo, hole_n;     // tokens [hole_lo, hole_lo + hole_n) are evicted: streamed, never attended to
 };
@@ -104,12 +110,14 @@ __device__ __forceinline__ sk_seg sk_make_seg(const sk_launch& P, const sk_work&
         g.table = P.g.tables + w.tbl_off; g.blk_stride = P.g.blk_stride;
         g.v_off = P.g.v_off; g.B = P.g.B; g.log2B = P.g.log2B;
         g.begin = w.kv_begin; g.end = w.kv_end; g.pos_shift = 0;
+        g.step = w.kv_step > 0 ? w.kv_step : 64;
         g.hole_lo = w.hole_lo; g.hole_n = w.hole_hi - w.hole_lo;
     } else {
         g.base = P.g.eph + (int64_t)w.kv_head * P.g.eph_head_stride;
         g.table = P.g.eph_ident + (s == 1 ? w.eph_blk[0] : w.eph_blk[1] + (s - 2) * w.sub_blocks); g.blk_stride = P.g.eph_blk_stride;
         g.v_off = P.g.eph_v_off; g.B = 16; g.log2B = 4;
         g.begin = 0; g.end = (s == 1 ? w.eph_cnt[0] : w.eph_cnt[1]); g.pos_shift = (s == 1 ? w.eph_pos0[0] : w.eph_pos0[1]);
+        g.step = 64;
         g.hole_lo = 0; g.hole_n = 0;
     }
     return g;
@@ -341,8 +349,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
     for (int s = 0; s < 2 + n_sub; ++s) {
         sk_seg g = sk_make_seg(P, w, s);
         if (g.end <= g.begin) continue;
-        const int ntiles = (g.end - g.begin + SK_TILE - 1) / SK_TILE;
-        const int niter = (ntiles + TPI - 1) / TPI;
+        const int niter = (g.end - g.begin + g.step - 1) / g.step;      // iteration i: keys from g.begin + i * g.step
         const int last_group = (g.end - 1) & ~15;
         // last position of the segment this wave's rows may see; nothing of another sequence's segment
         const int seg_last_pos = (s >= 2 && s - 2 != wave_sub) ? (int)0x80000000 : g.end - 1 + g.pos_shift;
@@ -363,9 +370,9 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
         bf16x8 pb[TPW][2];         // its P^T operands
 
         // first key position of the wave's tiles of iteration `it`, and whether it has work there
-        auto first_pos = [&](const int it) __attribute__((always_inline)) { return g.begin + (it * TPI + ph * TPW) * SK_TILE + g.pos_shift; };
+        auto first_pos = [&](const int it) __attribute__((always_inline)) { return g.begin + it * g.step + ph * TPW * SK_TILE + g.pos_shift; };
         auto is_active = [&](const int it) __attribute__((always_inline)) {
-            return wave_has_rows && it * TPI + ph * TPW < ntiles && first_pos(it) <= lim_wave_max;
+            return wave_has_rows && g.begin + it * g.step + ph * TPW * SK_TILE < g.end && first_pos(it) <= lim_wave_max;
         };
 
         // S^T = K Q^T, TPW independent accumulator chains
@@ -488,7 +495,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
                 if (a < niter) {
 #pragma unroll
                     for (int p = 0; p < TPI; ++p) {
-                        const int t0 = g.begin + (a * TPI + p) * SK_TILE;
+                        const int t0 = g.begin + a * g.step + p * SK_TILE;
                         const sk_tile_blocks tb = sk_lookup_tile(g, t0, last_group);
                         sk_issue_tile<US>(g, t0, last_group, tb, unit_base + SK_SLOT_OFF(a, p), koff, voff);
                     }
@@ -498,7 +505,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
             sk_tile_blocks nb[TPI];
 #pragma unroll
             for (int p = 0; p < TPI; ++p)
-                nb[p] = sk_lookup_tile(g, g.begin + ((NSS - 1) * TPI + p) * SK_TILE, last_group);
+                nb[p] = sk_lookup_tile(g, g.begin + (NSS - 1) * g.step + p * SK_TILE, last_group);
 
             // STAGE is the ring slot the iteration reads; the slot read by the previous iteration is
             // refilled with iteration it + NSS - 1.
@@ -514,12 +521,12 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
                 if (it + NSS - 1 < niter) {
 #pragma unroll
                     for (int p = 0; p < TPI; ++p)
-                        sk_issue_tile<US>(g, g.begin + ((it + NSS - 1) * TPI + p) * SK_TILE, last_group, nb[p],
+                        sk_issue_tile<US>(g, g.begin + (it + NSS - 1) * g.step + p * SK_TILE, last_group, nb[p],
                                                        unit_base + SK_SLOT_OFF((STAGE + NSS - 1) % NSS, p), koff, voff);
                     if (it + NSS < niter) {
 #pragma unroll
                         for (int p = 0; p < TPI; ++p)
-                            nb[p] = sk_lookup_tile(g, g.begin + ((it + NSS) * TPI + p) * SK_TILE, last_group);
+                            nb[p] = sk_lookup_tile(g, g.begin + (it + NSS) * g.step + p * SK_TILE, last_group);
                     }
                 }
                 if (!is_active(it)) return;
@@ -563,12 +570,12 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
 #pragma unroll
             for (int a = 0; a < 3; ++a) {
                 if (a < ahead && a < niter) {
-                    const int t0 = g.begin + (a * TPI + my_tile) * SK_TILE;
+                    const int t0 = g.begin + a * g.step + my_tile * SK_TILE;
                     const sk_tile_blocks tb = sk_lookup_tile(g, t0, last_group);
                     sk_issue_tile<US>(g, t0, last_group, tb, unit_base + SK_SLOT_OFF(a, my_tile), koff, voff);
                 }
             }
-            sk_tile_blocks nb = sk_lookup_tile(g, g.begin + (ahead * TPI + my_tile) * SK_TILE, last_group);
+            sk_tile_blocks nb = sk_lookup_tile(g, g.begin + ahead * g.step + my_tile * SK_TILE, last_group);
             {   // iteration 0 has landed: all but the loads of the later iterations issued above
                 const int issued = niter < ahead ? niter : ahead;
                 if (issued >= 3) SK_WAIT_VMCNT(2 * LPW); else if (issued == 2) SK_WAIT_VMCNT(LPW); else SK_WAIT_VMCNT(0);
@@ -581,9 +588,9 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
             auto refill = [&](const int j) __attribute__((always_inline)) {
                 const int i = j + ahead;
                 if (i < niter) {
-                    sk_issue_tile<US>(g, g.begin + (i * TPI + my_tile) * SK_TILE, last_group, nb,
+                    sk_issue_tile<US>(g, g.begin + i * g.step + my_tile * SK_TILE, last_group, nb,
                                                    unit_base + SK_SLOT_OFF(i & 3, my_tile), koff, voff);
-                    if (i + 1 < niter) nb = sk_lookup_tile(g, g.begin + ((i + 1) * TPI + my_tile) * SK_TILE, last_group);
+                    if (i + 1 < niter) nb = sk_lookup_tile(g, g.begin + (i + 1) * g.step + my_tile * SK_TILE, last_group);
                 }
             };
             // Matrix slot: eight groups of four matrix instructions, P V of the previous iteration

@@ -115,7 +115,7 @@ struct sk_pool {
     // Tuning switches, read from the environment once when the pool is created (see sk_pool_create).
     int target_wgs = kDefaultTargetWgs;
     bool target_wgs_set = false;
-    bool force_simple = false, no_256 = false, no_pack = false;
+    bool force_simple = false, no_256 = false, no_pack = false, no_interleave = false;
     // optional kernel timing
     bool profiling = false;
     std::vector<hipEvent_t> prof_ev;     // triples: before attention, after attention, after combine
@@ -258,6 +258,10 @@ int run_regular(sk_pool* p, int32_t id, const void* q, int64_t n_tok, int32_t po
     L.n_splits = (int32_t)parts;
     L.eph_blk[0] = 0; L.eph_cnt[0] = eph_cnt; L.eph_pos0[0] = eph_pos0;
     L.hole_lo = (int32_t)p->sessions[id].frozen; L.hole_hi = (int32_t)p->sessions[id].win;
+    // Small queries (at most 64 rows per KV head; every cached token visible to every row): the splits
+    // interleave their 64-key pieces.  Measured 3-5 % faster there (16 tokens at 128K: 99.5 -> 96 us),
+    // 2-3 % slower for the 128-row instance, which keeps contiguous chunks.
+    L.interleave = (!p->no_interleave && v.id == SK_KV_MFMA64 && S > 1 && kv_len <= (int64_t)pos0) ? 1 : 0;
     const int32_t wgs = int32_t(base_wgs * parts);
     hipEvent_t* pe = prof_begin(p, st);
     int e = sk_launch_attention(L, v.id, wgs, st);
@@ -638,6 +642,7 @@ int sk_pool_create(const sk_pool_desc* desc, sk_pool** out)
     p->force_simple = env_on("SK_FORCE_SIMPLE");
     p->no_256 = env_on("SK_NO_256");
     p->no_pack = env_on("SK_NO_PACK");
+    p->no_interleave = env_on("SK_NO_INTERLEAVE");
     if (!meta_only) {
         hipError_t e = hipHostMalloc((void**)&p->ring, kMetaBytes * kRingSlots, hipHostMallocDefault);
         if (e != hipSuccess) { g_last_hip = (int)e; delete p; return SK_E_HIP; }

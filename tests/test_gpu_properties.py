@@ -11,7 +11,7 @@ import torch
 
 import paper_2605_13784_amd as sk
 from workloads import synth
-from gpu_common import Pair, compare, dev
+from gpu_common import TOL, Pair, compare, dev
 
 pytestmark = pytest.mark.gpu
 SHAPE = synth.CFG2
@@ -117,7 +117,8 @@ def test_extend_then_clear_equals_noncommitting_query():
     torch.cuda.synchronize()
     assert pr.pool.sk_session_length(sid) == 1000 and pr.pool.sk_pool_blocks_free() == free0
     assert torch.equal(k0, k1) and torch.equal(v0, v1)
-    assert float((oa - ob).abs().max()) <= 2e-3 and float((la - lb).abs().max()) <= 1e-4
+    # two evaluations in different key orders: each LSE carries its own rounding of the weights
+    assert float((oa - ob).abs().max()) <= 2e-3 and float((la - lb).abs().max()) <= TOL[SHAPE.dtype]["lse"]
     # the session keeps working after the truncate: next append lands on the same positions
     q2, k2, v2 = _stream(gen, 50)
     pr.append(sid, q2, k2, v2, name="append after truncate")
