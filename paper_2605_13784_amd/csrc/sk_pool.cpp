@@ -260,8 +260,10 @@ int run_regular(sk_pool* p, int32_t id, const void* q, int64_t n_tok, int32_t po
     L.hole_lo = (int32_t)p->sessions[id].frozen; L.hole_hi = (int32_t)p->sessions[id].win;
     // Small queries (at most 64 rows per KV head; every cached token visible to every row): the splits
     // interleave their 64-key pieces.  Measured 3-5 % faster there (16 tokens at 128K: 99.5 -> 96 us),
-    // 2-3 % slower for the 128-row instance, which keeps contiguous chunks.
-    L.interleave = (!p->no_interleave && v.id == SK_KV_MFMA64 && S > 1 && kv_len <= (int64_t)pos0) ? 1 : 0;
+    // 2-3 % slower for the 128-row instance, which keeps contiguous chunks; with blocks of 256 tokens
+    // (where a V^T row of a block spans several pieces) 18 % slower, hence the limit on the block size.
+    L.interleave = (!p->no_interleave && v.id == SK_KV_MFMA64 && p->d.block_tokens <= 64 && S > 1 &&
+                    kv_len <= (int64_t)pos0) ? 1 : 0;
     const int32_t wgs = int32_t(base_wgs * parts);
     hipEvent_t* pe = prof_begin(p, st);
     int e = sk_launch_attention(L, v.id, wgs, st);
