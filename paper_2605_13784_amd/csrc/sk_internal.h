@@ -9,10 +9,12 @@
 //
 // kv_mem layout, chosen for gfx950: [kv_head][block][ K | V ] with, per (head, block),
 //   K : [block_tokens][head_dim]            one 128/256-byte row per token
-//   V : bf16 pools  [head_dim][block_tokens]  (transposed: 8 consecutive tokens of one
-//                   dimension are one 16-byte MFMA operand for the P*V contraction)
+//   V : bf16 pools  [block_tokens / 16][head_dim][16]  (transposed within each 16-token group:
+//                   8 consecutive tokens of one dimension are one 16-byte MFMA operand for the
+//                   P*V contraction)
 //       f32 pools   [block_tokens][head_dim]
-// so a 16-token group of one head is a contiguous 4 KiB (bf16, d=128) for K and for V, every
+// so a 16-token group of one head is a contiguous 4 KiB (bf16, d=128) for K and for V whatever
+// the block size, every
 // global load is a whole 128-byte line, and the blocks of one head (what one workgroup
 // streams) are contiguous when a session's table is in order.
 // The staging area for uncommitted (query-plane) K/V in the workspace has the same layout

@@ -228,7 +228,7 @@ __device__ __forceinline__ sk_tile_blocks sk_lookup_tile(const sk_seg& g, int t0
 //   K   : the wave fills LDS rows 16 j + 4 sub .. + 3 of group j; lane -> (row rr, chunk position),
 //         source chunk (position ^ rr):        koff = rr * 256 + ((lane & 15) ^ rr) * 16
 //   V^T : the wave fills dims 32 sub .. + 31 of group j; lane -> (dim dd, half position),
-//         source half (position ^ bit 3 of dd): voff = V offset in the block + dd * 2B + (half ^ ((dd >> 3) & 1)) * 16
+//         source half (position ^ bit 3 of dd): voff = V offset in the block + dd * 32 + (half ^ ((dd >> 3) & 1)) * 16
 // and the 16-key group's offset inside a block of more than 16 tokens is added to those.
 // In LDS the sixteen 1 KiB units of a tile (K units 0-7, V^T units 8-15) lie US bytes apart, with
 // the same unit of the other tiles of the ring in between; `unit_addr` is the address of unit `sub`.
@@ -241,8 +241,8 @@ __device__ __forceinline__ void sk_issue_group(const sk_seg& g, int t0, int last
     const unsigned char* bb = g.base + ((uint64_t)blk << (g.log2B + 9));
     if (g.B > 16) {
         const unsigned slot0 = (unsigned)tg & (unsigned)(g.B - 1);
-        koff += slot0 << 8;
-        voff += slot0 << 1;
+        koff += slot0 << 8;          // K: 256 bytes per token
+        voff += slot0 << 8;          // V^T: 4 KiB per 16-token group
     }
     sk_dma16<J * 4 * US>(bb, koff, unit_addr);
     sk_dma16<(8 + J * 4) * US>(bb, voff, unit_addr);
@@ -360,7 +360,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
         // lane-dependent parts of the DMA source addresses for this segment
         const unsigned koff = (unsigned)((sub * 4 + (lane >> 4)) * 256 + (((lane & 15) ^ (sub * 4 + (lane >> 4))) << 4));
         const int vdd = sub * 32 + (lane >> 1);
-        const unsigned voff = (unsigned)(g.v_off + vdd * (2 * g.B) + ((((lane & 1) ^ ((vdd >> 3) & 1))) << 4));
+        const unsigned voff = (unsigned)(g.v_off + vdd * 32 + ((((lane & 1) ^ ((vdd >> 3) & 1))) << 4));
 
         // ---- the three steps of one iteration (64 keys) for this wave; the ring slot is a
         // compile-time constant so that it folds into the offset field of the LDS instructions ----
@@ -825,7 +825,7 @@ __global__ __launch_bounds__(256) void sk_attn_simple(const sk_launch P)
                     int slot = tok & (g.B - 1);
                     if (BF16) {
                         kx = bf16_bits_to_f32(((const uint16_t*)bb)[(size_t)slot * d + t]);
-                        vx = bf16_bits_to_f32(((const uint16_t*)(bb + g.v_off))[(size_t)t * g.B + slot]);
+                        vx = bf16_bits_to_f32(((const uint16_t*)(bb + g.v_off))[((size_t)(slot >> 4) * d + t) * 16 + (slot & 15)]);
                     } else {
                         kx = ((const float*)bb)[(size_t)slot * d + t];
                         vx = ((const float*)(bb + g.v_off))[(size_t)slot * d + t];
@@ -995,7 +995,7 @@ __global__ __launch_bounds__(256) void sk_combine(const sk_launch P)
 // ---------------------------------------------------------------------------------------------
 // K/V commit.  One workgroup per (destination 16-token group, KV head).  Pure bit copies through
 // integer lanes.  K rows are copied as 16-byte chunks; V is copied likewise for f32 pools and
-// transposed through LDS for bf16 pools ([dim][token]).
+// transposed through LDS for bf16 pools ([dim][token] within each 16-token group).
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ void sk_scatter_item(const sk_geom& g, const void* k, const void* v, const sk_scatter& it,
                                                 const int head, int32_t* tables_rw, unsigned char* kv_rw, unsigned char* eph_rw)
@@ -1004,7 +1004,6 @@ __device__ __forceinline__ void sk_scatter_item(const sk_geom& g, const void* k,
     const int tid = threadIdx.x;
     const int d = g.d, elem = g.elem;
     const int rowbytes = d * elem;
-    const int Bd = it.to_eph ? 16 : g.B;
     unsigned char* dst = (it.to_eph ? eph_rw : kv_rw) + it.dst_off +
                          (int64_t)head * (it.to_eph ? g.eph_head_stride : g.head_stride);
     const int v_off = it.to_eph ? g.eph_v_off : g.v_off;
@@ -1031,7 +1030,7 @@ __device__ __forceinline__ void sk_scatter_item(const sk_geom& g, const void* k,
         // Slots of the 16-token group behind the last committed token are zero-filled, so that a
         // key the attention kernel masks out never multiplies 0 by leftover bits.
         const int first = it.dst_slot0 & 15;            // position inside the 16-token group
-        uint16_t* vd = (uint16_t*)(dst + v_off) + (it.dst_slot0 - first);
+        uint16_t* vd = (uint16_t*)(dst + v_off) + (size_t)(it.dst_slot0 >> 4) * d * 16;     // the group's [dim][16 tokens]
         if (first == 0) {
             // from the start of the group: 2 lanes per dimension, 8 tokens (16 bytes) each
             for (int idx = tid; idx < 2 * d; idx += 256) {
@@ -1044,13 +1043,13 @@ __device__ __forceinline__ void sk_scatter_item(const sk_geom& g, const void* k,
                     const uint32_t hi = s0 + 1 < it.count ? vt[s0 + 1][t] : 0u;
                     wv[j] = lo | (hi << 16);
                 }
-                *(uint4*)(vd + (size_t)t * Bd + half * 8) = make_uint4(wv[0], wv[1], wv[2], wv[3]);
+                *(uint4*)(vd + (size_t)t * 16 + half * 8) = make_uint4(wv[0], wv[1], wv[2], wv[3]);
             }
         } else {
             const int span = 16 - first;                 // slots first..15: tokens, then zeros
             for (int idx = tid; idx < span * d; idx += 256) {
                 const int t = idx / span, jj = idx % span;
-                vd[(size_t)t * Bd + first + jj] = jj < it.count ? vt[jj][t] : (uint16_t)0;
+                vd[(size_t)t * 16 + first + jj] = jj < it.count ? vt[jj][t] : (uint16_t)0;
             }
         }
     }
@@ -1089,7 +1088,7 @@ __global__ __launch_bounds__(256) void sk_gather_kernel(const sk_geom g, int32_t
         const unsigned char* bb = g.kv + (int64_t)blk * g.blk_stride + (int64_t)head * g.head_stride;
         if (g.elem == 2) {
             ((uint16_t*)k_out)[idx] = ((const uint16_t*)bb)[(size_t)slot * d + t];
-            ((uint16_t*)v_out)[idx] = ((const uint16_t*)(bb + g.v_off))[(size_t)t * g.B + slot];
+            ((uint16_t*)v_out)[idx] = ((const uint16_t*)(bb + g.v_off))[((size_t)(slot >> 4) * d + t) * 16 + (slot & 15)];
         } else {
             ((uint32_t*)k_out)[idx] = ((const uint32_t*)bb)[(size_t)slot * d + t];
             ((uint32_t*)v_out)[idx] = ((const uint32_t*)(bb + g.v_off))[(size_t)slot * d + t];

@@ -260,10 +260,9 @@ int run_regular(sk_pool* p, int32_t id, const void* q, int64_t n_tok, int32_t po
     L.hole_lo = (int32_t)p->sessions[id].frozen; L.hole_hi = (int32_t)p->sessions[id].win;
     // Small queries (at most 64 rows per KV head; every cached token visible to every row): the splits
     // interleave their 64-key pieces.  Measured 3-5 % faster there (16 tokens at 128K: 99.5 -> 96 us),
-    // 2-3 % slower for the 128-row instance, which keeps contiguous chunks; with blocks of 256 tokens
-    // (where a V^T row of a block spans several pieces) 18 % slower, hence the limit on the block size.
-    L.interleave = (!p->no_interleave && v.id == SK_KV_MFMA64 && p->d.block_tokens <= 64 && S > 1 &&
-                    kv_len <= (int64_t)pos0) ? 1 : 0;
+    // 2-3 % slower for the 128-row instance, which keeps contiguous chunks.  Larger blocks gain more
+    // (16 tokens at 128K: 98 / 96 / 92 us with 16- / 64- / 256-token blocks).
+    L.interleave = (!p->no_interleave && v.id == SK_KV_MFMA64 && S > 1 && kv_len <= (int64_t)pos0) ? 1 : 0;
     const int32_t wgs = int32_t(base_wgs * parts);
     hipEvent_t* pe = prof_begin(p, st);
     int e = sk_launch_attention(L, v.id, wgs, st);
@@ -1131,7 +1130,7 @@ int64_t sk_pool_element_offset(const sk_pool* p, int64_t block, int32_t kv_head,
     int64_t off = block * p->L.blk_stride + int64_t(kv_head) * p->L.head_stride;
     if (!is_v) return off + (int64_t(slot) * p->d.head_dim + dim) * p->L.elem;
     off += p->L.v_off;
-    if (p->d.dtype == SK_BF16) return off + (int64_t(dim) * p->d.block_tokens + slot) * p->L.elem;
+    if (p->d.dtype == SK_BF16) return off + ((int64_t(slot >> 4) * p->d.head_dim + dim) * 16 + (slot & 15)) * p->L.elem;
     return off + (int64_t(slot) * p->d.head_dim + dim) * p->L.elem;
 }
 

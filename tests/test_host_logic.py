@@ -143,7 +143,12 @@ def test_element_offsets_describe_the_layout():
     assert p.sk_pool_element_offset(1, 0, False, 0, 0) == blk
     assert p.sk_pool_element_offset(0, 1, False, 0, 0) == 4 * blk          # heads are outermost
     assert p.sk_pool_element_offset(0, 0, False, 3, 5) == (3 * 128 + 5) * e
-    assert p.sk_pool_element_offset(0, 0, True, 3, 5) == 16 * 128 * e + (5 * 16 + 3) * e    # V is [dim][token]
+    assert p.sk_pool_element_offset(0, 0, True, 3, 5) == 16 * 128 * e + (5 * 16 + 3) * e    # V is [dim][token] per 16-token group
+    big = meta_pool(n_blocks=4, block_tokens=64)
+    v0 = 64 * 128 * e
+    assert big.sk_pool_element_offset(0, 0, True, 3, 5) == v0 + (5 * 16 + 3) * e
+    assert big.sk_pool_element_offset(0, 0, True, 16 + 3, 5) == v0 + (128 * 16 + 5 * 16 + 3) * e   # next group: 4 KiB on
+    assert big.sk_pool_element_offset(0, 0, True, 63, 127) == v0 + (3 * 128 * 16 + 127 * 16 + 15) * e == 2 * v0 - e
     assert p.sk_pool_element_offset(4, 0, False, 0, 0) == -1
     f = meta_pool(dtype="f32", n_q_heads=4, n_kv_heads=4, head_dim=64, n_blocks=4)
     assert f.sk_pool_element_offset(0, 0, True, 3, 5) == 16 * 64 * 4 + (3 * 64 + 5) * 4       # V is [token][dim]
