@@ -44,14 +44,13 @@ def _build(pool, sid, ref, n, shape, gen, piece=2048):
     ref.K = np.concatenate([ref.K] + Ks); ref.V = np.concatenate([ref.V] + Vs)
 
 
-@pytest.mark.parametrize("n,L,nq,n_rows", [(32768, 256, 32, 64), (131072, 512, 16, 24)])
-def test_single_session_full_context(n, L, nq, n_rows):
+@pytest.mark.parametrize("n,L,nq,n_rows,B", [(32768, 256, 32, 64, 16), (131072, 512, 16, 24, 16), (131072, 512, 16, 24, 256)])
+def test_single_session_full_context(n, L, nq, n_rows, B):
     """Workloads 2 and 3: one Llama-3-8B-shaped layer at 32,768 / 131,072 cached tokens; the append
     that reaches that length, then queries with the library's own split choice (what bench.py times)."""
     shape = synth.CFG2
     gen = synth.generator(2 if n == 32768 else 3, stream=20)
     rng = np.random.default_rng(n)
-    B = 16
     pool = sk.Pool(shape.dtype, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, B, n // B + 8, max_sessions=1,
                    max_batch_tokens=2048)
     ref = oracle.OracleSession(shape.dtype, shape.n_q_heads, shape.n_kv_heads, shape.head_dim)
