@@ -236,7 +236,10 @@ def stream_workload(sk, name, args, steps, warmup, calibrate=False):
     roof_a = {"kernel": "sk_attn_bf16_d128 (append, causal over cache + chunk)", "bound": "mfma",
               "achieved": af / (a_kernel_us * 1e-6) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
               "frac": af / (a_kernel_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, **hbm("append"),
-              "avg_kernel_us": a_kernel_us, "algorithmic_flops": af}
+              "avg_kernel_us": a_kernel_us, "algorithmic_flops": af,
+              "timing": "HIP events recorded by the library around the kernel, in a repeat of the timed steps; the "
+                        "events leave idle gaps between the kernels, after which a kernel of this power-limited "
+                        "chip runs 13-15 % faster than back to back (profiles/bench_cfg2_attention_kernels.md)"}
     return {
         "tokens_per_s": (L + nq) * steps / wall, "ms_per_step": wall * 1e3 / steps,
         "config": {"workload": name, "n_q_heads": shape.n_q_heads, "n_kv_heads": shape.n_kv_heads,
