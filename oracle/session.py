@@ -200,7 +200,7 @@ OP_APPEND, OP_QUERY_A, OP_QUERY_B = 0, 1, 2
 
 
 class OraclePool:
-    """Several isolated sessions (Sec. 3.4 "session isolation") and the ragged step
+    """Several isolated sessions (Sec. 3.4) and the ragged step
     that the multi-tenant scheduler of Sec. 3.7 issues: a mix of appends and queries
     over distinct sessions, equal by definition to issuing them one at a time."""
 

@@ -224,7 +224,7 @@ def test_large_scores_need_max_subtraction_and_needle_retrieval():
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_incremental_append_equals_one_shot_bit_identical(dtype):
     """Appending D_1..D_k one at a time gives every token the output of one causal pass over
-    [S; D_1; ..; D_k] (Sec. 2 (i)-(iii); Sec. 3.4 'only the delta is processed')."""
+    [S; D_1; ..; D_k] (Sec. 2 (i)-(iii); Sec. 3.4)."""
     Hq, Hkv, d, T = 4, 2, 8, 40
     rng = np.random.default_rng(6)
     q, k, v = _rand(rng, (T, Hq, d), dtype), _rand(rng, (T, Hkv, d), dtype), _rand(rng, (T, Hkv, d), dtype)
@@ -395,8 +395,8 @@ def test_bf16_inputs_are_widened_exactly():
 def test_eviction_attends_over_frozen_prefix_and_retained_window_only():
     """Region 0 frozen, Region 1 FIFO-evicted (Sec. 3.3; Alg. 1 evict_oldest): after evicting, every
     row equals a pure-Python softmax over [frozen tokens ; retained tokens] in their original order;
-    a needle in the frozen region is still retrieved, one in the evicted range is lost (the paper's
-    "attention over that data is lost"), evicting nothing changes nothing."""
+    a needle in the frozen region is still retrieved, one in the evicted range is lost (Sec. 5.3:
+    evicted data can no longer be attended to), evicting nothing changes nothing."""
     Hq, Hkv, d, n, nf, ne = 2, 1, 4, 20, 5, 7
     rng = np.random.default_rng(11)
     K, V = _rand(rng, (n, Hkv, d), "f32"), _rand(rng, (n, Hkv, d), "f32")
@@ -439,7 +439,7 @@ def test_eviction_attends_over_frozen_prefix_and_retained_window_only():
 
 def test_fork_is_a_prefix_by_value():
     """fork(n) reads like the source cut at n tokens (brute force on the first n tokens), and the
-    two sessions are isolated afterwards (Sec. 3.4 "isolation between sessions")."""
+    two sessions are isolated afterwards (the session isolation of Sec. 3.4)."""
     Hq, Hkv, d, n, n_prefix = 2, 2, 3, 9, 6
     rng = np.random.default_rng(12)
     K, V = _rand(rng, (n, Hkv, d), "f32"), _rand(rng, (n, Hkv, d), "f32")
@@ -458,3 +458,125 @@ def test_fork_is_a_prefix_by_value():
     t.evict_oldest(3)
     np.testing.assert_array_equal(s.query(q)[0], before[0])
     assert s.length == n and t.length == n_prefix + 2 - 3
+
+
+def test_truncate_keeps_exactly_the_first_p_tokens():
+    """SeqRemove(s, p, infinity) of Sec. 3.9.3: after truncate(p) every row equals a pure-Python
+    softmax over the first p committed tokens (an off-by-one in the cut fails: p-1 and p+1 keys give
+    other numbers), appends continue at position p, and the literal Strip / Extend / Clear cycle
+    (append, read, truncate back) returns what the non-committing query returns and leaves the cache
+    as it was."""
+    Hq, Hkv, d, n = 2, 1, 3, 11
+    rng = np.random.default_rng(13)
+    K, V = _rand(rng, (n, Hkv, d), "f32"), _rand(rng, (n, Hkv, d), "f32")
+    q = _rand(rng, (2, Hq, d), "f32")
+    scale = 1.0 / math.sqrt(d)
+    for p in (n, 7, 1):
+        s = OracleSession("f32", Hq, Hkv, d)
+        s.append(np.zeros((n, Hq, d), np.float32), K, V)
+        s.truncate(p)
+        assert s.length == p
+        np.testing.assert_array_equal(s.cache()[0], K[:p])
+        np.testing.assert_array_equal(s.cache()[1], V[:p])
+        o, l = s.query(q)
+        for i in range(2):
+            for h in range(Hq):
+                ro, rl = _brute_row(q[i, h].tolist(), [K[j, 0].tolist() for j in range(p)],
+                                    [V[j, 0].tolist() for j in range(p)], scale)
+                np.testing.assert_allclose(o[i, h], ro, rtol=1e-12, atol=1e-13)
+                assert abs(l[i, h] - rl) < 1e-12
+                if 1 < p < n:      # the neighbours of the cut are different numbers, so the check can fail
+                    for wrong in (p - 1, p + 1):
+                        wo, _ = _brute_row(q[i, h].tolist(), [K[j, 0].tolist() for j in range(wrong)],
+                                           [V[j, 0].tolist() for j in range(wrong)], scale)
+                        assert np.abs(np.array(wo) - o[i, h]).max() > 1e-6
+        # the next append lands at position p: its first row sees p + 1 keys
+        k2, v2, q2 = _rand(rng, (2, Hkv, d), "f32"), _rand(rng, (2, Hkv, d), "f32"), _rand(rng, (2, Hq, d), "f32")
+        o2, _ = s.append(q2, k2, v2)
+        ro, _ = _brute_row(q2[0, 1].tolist(), [K[j, 0].tolist() for j in range(p)] + [k2[0, 0].tolist()],
+                           [V[j, 0].tolist() for j in range(p)] + [v2[0, 0].tolist()], scale)
+        np.testing.assert_allclose(o2[0, 1], ro, rtol=1e-12, atol=1e-13)
+        assert s.length == p + 2
+    # Extend then Clear == non-committing query (Sec. 3.9.3), cache restored bit for bit
+    s = OracleSession("f32", Hq, Hkv, d)
+    s.append(np.zeros((n, Hq, d), np.float32), K, V)
+    qq, kq, vq = _rand(rng, (3, Hq, d), "f32"), _rand(rng, (3, Hkv, d), "f32"), _rand(rng, (3, Hkv, d), "f32")
+    pure = s.query(qq, kq, vq)
+    lit = s.append(qq, kq, vq)
+    s.truncate(n)
+    np.testing.assert_array_equal(pure[0], lit[0])
+    np.testing.assert_array_equal(pure[1], lit[1])
+    np.testing.assert_array_equal(s.cache()[0], K)
+    with pytest.raises(ValueError):
+        s.truncate(n + 1)
+    with pytest.raises(ValueError):
+        s.truncate(-1)
+    s.truncate(0)
+    assert s.length == 0
+    with pytest.raises(ZeroDivisionError):
+        s.query(q)
+
+
+def test_truncate_and_fork_below_the_frozen_length_clip_it():
+    """Region 0 cannot be longer than the session (Sec. 3.3): cutting a session, or forking a prefix,
+    below n_frozen leaves a frozen region of the new length, so a later eviction starts behind it
+    (brute force over the expected survivors); cutting above n_frozen leaves it alone."""
+    Hq, Hkv, d, n, nf = 1, 1, 2, 12, 6
+    rng = np.random.default_rng(14)
+    K, V = _rand(rng, (n, Hkv, d), "f32"), _rand(rng, (n, Hkv, d), "f32")
+    q = _rand(rng, (1, Hq, d), "f32")
+    k2, v2 = _rand(rng, (5, Hkv, d), "f32"), _rand(rng, (5, Hkv, d), "f32")
+    scale = 1.0 / math.sqrt(d)
+
+    def fresh():
+        s = OracleSession("f32", Hq, Hkv, d)
+        s.append(np.zeros((n, Hq, d), np.float32), K, V)
+        s.freeze(nf)
+        return s
+
+    def expect(s, keys, vals):
+        o, l = s.query(q)
+        ro, rl = _brute_row(q[0, 0].tolist(), [x.tolist() for x in keys], [x.tolist() for x in vals], scale)
+        np.testing.assert_allclose(o[0, 0], ro, rtol=1e-12, atol=1e-13)
+        assert abs(l[0, 0] - rl) < 1e-12
+
+    # cut below the frozen length: frozen becomes 4; five new tokens, evict two -> the new tokens 0,1 go
+    for make in (lambda: (lambda s: (s.truncate(4), s)[1])(fresh()), lambda: fresh().fork(4)):
+        s = make()
+        assert s.n_frozen == 4 and s.length == 4
+        s.append(np.zeros((5, Hq, d), np.float32), k2, v2)
+        s.evict_oldest(2)
+        expect(s, list(K[:4, 0]) + list(k2[2:, 0]), list(V[:4, 0]) + list(v2[2:, 0]))
+        with pytest.raises(ValueError):
+            s.evict_oldest(4)                      # only three unfrozen tokens are left
+    # cut above it: frozen stays 6; evicting two drops tokens 6 and 7
+    for make in (lambda: (lambda s: (s.truncate(9), s)[1])(fresh()), lambda: fresh().fork(9)):
+        s = make()
+        assert s.n_frozen == nf and s.length == 9
+        s.evict_oldest(2)
+        expect(s, list(K[:6, 0]) + list(K[8:9, 0]), list(V[:6, 0]) + list(V[8:9, 0]))
+    # the source of a fork keeps its own frozen length
+    s = fresh(); s.fork(2)
+    assert s.n_frozen == nf and s.length == n
+
+
+def test_pool_destroy_forgets_the_session_and_nothing_else():
+    """Sec. 3.4 session life cycle: a destroyed session is gone (its id is no longer served), the
+    others still read exactly what they read before, and a new session starts empty."""
+    pool = OraclePool("f32", 2, 1, 2)
+    a, b = pool.create(), pool.create()
+    rng = np.random.default_rng(15)
+    for sid in (a, b):
+        pool.sessions[sid].append(_rand(rng, (3, 2, 2), "f32"), _rand(rng, (3, 1, 2), "f32"), _rand(rng, (3, 1, 2), "f32"))
+    q = _rand(rng, (1, 2, 2), "f32")
+    before = pool.sessions[b].query(q)
+    pool.destroy(a)
+    assert a not in pool.sessions and b in pool.sessions
+    with pytest.raises(KeyError):
+        pool.batch_step([a], [OP_QUERY_A], [0, 1], q, None, None)
+    with pytest.raises(KeyError):
+        pool.destroy(a)
+    after = pool.sessions[b].query(q)
+    np.testing.assert_array_equal(before[0], after[0])
+    c = pool.create()
+    assert c != b and pool.sessions[c].length == 0
