@@ -33,11 +33,15 @@ def build(force: bool = True, verbose: bool = False) -> str:
     cmd = [hipcc] + HIPCC_FLAGS + ["-Rpass-analysis=kernel-resource-usage", "-o", tmp] + [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:
         print(" ".join(cmd))
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + r.stdout + r.stderr)
-    check_no_spills(r.stderr)
-    os.replace(tmp, LIB)
+    try:
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + r.stdout + r.stderr)
+        check_no_spills(r.stderr)
+        os.replace(tmp, LIB)
+    finally:
+        if os.path.exists(tmp):          # a failed compile or a refused kernel leaves nothing behind
+            os.unlink(tmp)
     return LIB
 
 
@@ -58,3 +62,21 @@ def check_no_spills(remarks: str) -> None:
 
 if __name__ == "__main__":
     print(build(verbose=True))
+
+
+def build_host_check(driver_src: str, out: str) -> str:
+    """Builds an executable from `driver_src` plus the library's sources with AddressSanitizer and
+    UndefinedBehaviorSanitizer on the HOST pass only (the device code is compiled as always and never
+    runs: the driver uses metadata-only pools).  The sanitizer runtime is linked into the executable,
+    so it runs as it is, with no preloaded library."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    san = []
+    for f in ("-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer"):
+        san += ["-Xarch_host", f]
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-g", "-std=c++17"] + san + \
+          ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-o", out, driver_src] + \
+          [os.path.join(CSRC, s) for s in SOURCES]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc (sanitized host build) failed:\n" + r.stdout + r.stderr)
+    return out
