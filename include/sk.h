@@ -4,13 +4,12 @@
  * One attention layer of the paper's stateful-session model: a short segment of
  * new tokens attends against a long, persistent, per-session KV cache.
  *
- *   data plane  (Alg. 1, "K.append(Forward(tokens, K))"; Sec. 3.4 "only the delta
- *                is processed and appended"): sk_session_append commits the chunk's
- *                K/V into the session cache and the chunk attends causally over
- *                cache + chunk;
- *   query plane (Alg. 2, "Forward(tokens_q, K)"; Sec. 3.2 Eq. 2; Sec. 3.3 Region 2;
- *                Sec. 3.9.3 Extend/Clear): sk_session_query attends over the cache
- *                and commits nothing;
+ *   data plane  (Alg. 1, the append step; Sec. 3.4): sk_session_append commits the
+ *                chunk's K/V into the session cache and the chunk attends causally
+ *                over cache + chunk; nothing already cached is recomputed;
+ *   query plane (Alg. 2, the forward pass of the query tokens; Sec. 3.2 Eq. 2;
+ *                Sec. 3.3 Region 2; Sec. 3.9.3 Extend/Clear): sk_session_query
+ *                attends over the cache and commits nothing;
  *   both planes for many sessions in one step (Sec. 3.7 heterogeneous
  *                PREFILL+DECODE batches): sk_batch_step;
  *   a batch of registered questions sharing a prefix, evaluated against one session
@@ -38,9 +37,9 @@
  *   - Token-major layouts: q [T][Hq][d], k and v [T][Hkv][d], out [T][Hq][d],
  *     lse [T][Hq] (natural-log log-sum-exp of the scaled scores, float).
  *   - Precision, bf16 pools: scores, softmax statistics and accumulators are fp32; the softmax
- *     weights enter the second contraction rounded to bf16 and the row sums add those same
- *     rounded weights, so an output row is an exact convex combination of V rows and lse is
- *     within ln(1 + 2^-8) = 3.9e-3 of the exact value (far closer over long rows).  fp32 pools
+ *     weights enter the second contraction rounded to bf16 and the row sums that normalise the
+ *     output add those same rounded weights, so an output row is an exact convex combination of
+ *     V rows; lse is taken from the sum of the weights before rounding (fp32).  fp32 pools
  *     compute in fp32 throughout.
  */
 #ifndef SK_H
@@ -74,7 +73,7 @@ typedef struct sk_pool sk_pool;
 
 /*
  * Pool description, filled by the caller.  The pool is the paper's unified KV cache
- * (Sec. 3.7 "cells", Sec. 3.10.1) for ONE layer, cut into blocks of block_tokens
+ * (the cells of Sec. 3.7 and Sec. 3.10.1) for ONE layer, cut into blocks of block_tokens
  * tokens; a session owns a list of blocks (its block table).  Per token the pool
  * stores 2 * n_kv_heads * head_dim elements (Sec. 5.3 with d = n_kv_heads*head_dim).
  */
@@ -115,7 +114,14 @@ size_t sk_pool_workspace_bytes(const sk_pool_desc* desc);
  *   SK_NO_256=1        never the 256-row eight-wave instance of the bf16 kernel
  *   SK_NO_PACK=1       a question batch gives every question a row tile of its own
  *   SK_NO_INTERLEAVE=1 the splits of a query take contiguous chunks of the cache instead of
- *                      interleaved 64-key pieces */
+ *                      interleaved 64-key pieces
+ *   SK_NO_FUSE=1       single-session calls merge their split partials in a second kernel instead
+ *                      of inside the attention kernel (the same function merges a row either way:
+ *                      the results are bit-identical)
+ *   SK_WAIT_POLLS=n    how many polls (about 1 us each) a workgroup of a single-session call waits
+ *                      for the other workgroups of its row tile before it leaves the merge to the
+ *                      last one (default 256; 0: never wait)
+ *   SK_FUSE_LIST=1     batched calls merge inside the attention kernel too (last workgroup only) */
 int sk_pool_create(const sk_pool_desc* desc, sk_pool** out);
 /* Frees host metadata and the staging ring; caller memory is untouched.  The caller must
  * have synchronised the stream(s) the pool was used on. */
@@ -137,8 +143,13 @@ int sk_session_block_table(const sk_pool* pool, int32_t id, const int32_t** tabl
  * DATA PLANE (Alg. 1).  q [L][Hq][d], k,v [L][Hkv][d] DEVICE, pool dtype.  Commits k,v bit for
  * bit at positions n..n+L-1 of the session and writes, for chunk token i, attention over
  * positions 0..n+i.  out [L][Hq][d] of out_dtype (SK_F32 or the pool dtype); lse [L][Hq]
- * float or NULL.  q/out may be NULL together: commit only.  All or nothing: on error the
- * session, tables and free list are unchanged.  L == 0 is a no-op.  L <= max_batch_tokens.
+ * float or NULL.  q/out may be NULL together: commit only.  All or nothing: every check that
+ * can refuse the call runs before anything changes, and if a HIP call fails afterwards
+ * (SK_E_HIP) the host side is taken back, so on error the session's length and block table
+ * and the free list are as before (one exception that no caller can observe through the API
+ * other than by counting free blocks: when the session's last block was shared with a fork and
+ * the commit kernel was already enqueued, the session keeps its private copy of that block).
+ * L == 0 is a no-op.  L <= max_batch_tokens.
  */
 int sk_session_append(sk_pool* pool, int32_t id, const void* q, const void* k, const void* v,
                       int32_t L, void* out, int out_dtype, float* lse, void* hip_stream);
@@ -161,8 +172,9 @@ int sk_session_query(sk_pool* pool, int32_t id, const void* q, const void* k, co
  * cu_tokens[i]..cu_tokens[i+1]-1 of q/k/v/out/lse; op[i] is SK_OP_APPEND, SK_OP_QUERY_A
  * (cache only) or SK_OP_QUERY_B (own K/V, causal).  session_id, op, cu_tokens are HOST
  * arrays.  A session may appear once per step.  Equal to issuing the items one by one
- * (outputs up to summation order, cache bits exactly).  Block allocation is all or nothing
- * for the whole step.
+ * (outputs up to summation order, cache bits exactly).  All or nothing for the whole step,
+ * as for sk_session_append: a step that is refused, or that fails half way, leaves every
+ * session's length and block table and the free list as they were.
  */
 int sk_batch_step(sk_pool* pool, int32_t n_items, const int32_t* session_id, const int32_t* op,
                   const int32_t* cu_tokens, const void* q, const void* k, const void* v,
@@ -200,7 +212,7 @@ int sk_session_gather(const sk_pool* pool, int32_t id, int64_t first, int64_t co
 int sk_session_truncate(sk_pool* pool, int32_t id, int64_t new_length);
 
 /*
- * REGION 0 / REGION 1 (Sec. 3.3; Alg. 1 "if size + |tokens| > capacity: evict_oldest").
+ * REGION 0 / REGION 1 (Sec. 3.3; Alg. 1, the capacity check in front of the append).
  * sk_session_freeze marks the first n_frozen tokens of the session as Region 0: they are never
  * evicted.  n_frozen may only grow, must not exceed the session's length, and cannot change once
  * tokens have been evicted behind it (SK_E_INVAL).
@@ -253,6 +265,7 @@ int sk_top2(const float* logits, int32_t rows, int32_t vocab, int64_t row_stride
             void* workspace, size_t workspace_bytes,
             int32_t* idx1, int32_t* idx2, float* val1, float* val2, float* gap, void* hip_stream);
 
+
 /* Byte offset inside kv_mem of element (block, kv_head, is_v, slot, dim), so a harness can
  * address the pool without knowing the layout.  Negative on bad arguments. */
 int64_t sk_pool_element_offset(const sk_pool* pool, int64_t block, int32_t kv_head, int32_t is_v,
@@ -269,6 +282,8 @@ int sk_pool_get_stats(const sk_pool* pool, sk_pool_stats* out);
  * shapes only, not on how the cache was built): workgroups, splits per row tile, row tiles. */
 typedef struct sk_launch_info {
     int32_t workgroups, n_splits, row_tiles, kernel_variant;
+    int32_t fused_merge;   /* 1: the split partials were merged inside the attention kernel */
+    int32_t reserved[3];
 } sk_launch_info;
 int sk_pool_last_launch(const sk_pool* pool, sk_launch_info* out);
 
@@ -287,6 +302,19 @@ typedef struct sk_profile {
 int sk_pool_set_profiling(sk_pool* pool, int enable);
 int sk_pool_read_profile(sk_pool* pool, sk_profile* out, float* attention_ms_per_call /*HOST or NULL*/,
                          float* combine_ms_per_call /*HOST or NULL*/, int32_t capacity);
+
+/*
+ * Test hook for the error paths: the countdown-th time the pool reaches `site` from now on, that
+ * step fails as if its HIP call had (SK_E_HIP; SK_SITE_PLAN: SK_E_WORKSPACE) without touching the
+ * device.  Metadata-only pools pass the same sites, so the taking back of a half-done call can be
+ * checked without a GPU.  countdown 0 disarms.
+ */
+enum { SK_SITE_NONE = 0, SK_SITE_RING = 1,   /* waiting for a pinned upload slot */
+       SK_SITE_UPLOAD = 2,                   /* host-to-device copy of a list or block table */
+       SK_SITE_BLOCK_COPY = 3,               /* copy of a shared or partly filled block */
+       SK_SITE_SCATTER = 4, SK_SITE_ATTENTION = 5, SK_SITE_COMBINE = 6,   /* kernel launches */
+       SK_SITE_PLAN = 7 };                   /* the lists of a batched call do not fit */
+int sk_pool_inject_failure(sk_pool* pool, int32_t site, int32_t countdown);
 
 const char* sk_strerror(int status);     /* static storage */
 int sk_last_hip_error(void);             /* hipError_t of the last failing HIP call in this thread */

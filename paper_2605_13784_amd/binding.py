@@ -15,6 +15,8 @@ SK_F32, SK_BF16 = 0, 1
 SK_OP_APPEND, SK_OP_QUERY_A, SK_OP_QUERY_B = 0, 1, 2
 SK_POOL_METADATA_ONLY = 1
 
+SK_SITE_RING, SK_SITE_UPLOAD, SK_SITE_BLOCK_COPY, SK_SITE_SCATTER, SK_SITE_ATTENTION, SK_SITE_COMBINE, SK_SITE_PLAN = 1, 2, 3, 4, 5, 6, 7
+
 SK_OK = 0
 SK_E_INVAL, SK_E_SHAPE, SK_E_DTYPE, SK_E_NOMEM, SK_E_BADSESSION = -1, -2, -3, -4, -5
 SK_E_EMPTY, SK_E_WORKSPACE, SK_E_HIP, SK_E_NODEVICE = -6, -7, -8, -9
@@ -49,7 +51,8 @@ class sk_pool_stats(ctypes.Structure):
 
 class sk_launch_info(ctypes.Structure):
     _fields_ = [("workgroups", ctypes.c_int32), ("n_splits", ctypes.c_int32),
-                ("row_tiles", ctypes.c_int32), ("kernel_variant", ctypes.c_int32)]
+                ("row_tiles", ctypes.c_int32), ("kernel_variant", ctypes.c_int32),
+                ("fused_merge", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
 
 
 class sk_profile(ctypes.Structure):
@@ -65,6 +68,7 @@ EXPORTS = [
     "sk_pool_set_profiling", "sk_pool_read_profile",
     "sk_pool_element_offset", "sk_pool_get_stats", "sk_pool_last_launch", "sk_strerror",
     "sk_last_hip_error", "sk_version", "sk_top2_workspace_bytes", "sk_top2",
+    "sk_pool_inject_failure",
 ]
 
 _lib = None
@@ -109,6 +113,7 @@ def lib():
     L.sk_top2_workspace_bytes.restype = ctypes.c_size_t
     L.sk_top2_workspace_bytes.argtypes = [i32, i32]
     L.sk_top2.argtypes = [vp, i32, i32, i64, vp, ctypes.c_size_t, vp, vp, vp, vp, vp, vp]
+    L.sk_pool_inject_failure.argtypes = [vp, i32, i32]
     L.sk_pool_set_profiling.argtypes = [vp, ctypes.c_int]
     L.sk_pool_read_profile.argtypes = [vp, P(sk_profile), P(ctypes.c_float), P(ctypes.c_float), i32]
     L.sk_pool_element_offset.restype = i64
@@ -282,7 +287,10 @@ class Pool:
     def sk_pool_last_launch(self):
         s = sk_launch_info()
         _ck(lib().sk_pool_last_launch(self.h, ctypes.byref(s)), "sk_pool_last_launch")
-        return {k: getattr(s, k) for k, _ in s._fields_}
+        return {k: getattr(s, k) for k, _ in s._fields_ if k != "reserved"}
+
+    def sk_pool_inject_failure(self, site, countdown=1):
+        _ck(lib().sk_pool_inject_failure(self.h, int(site), int(countdown)), "sk_pool_inject_failure")
 
     def sk_pool_element_offset(self, block, kv_head, is_v, slot, dim):
         return int(lib().sk_pool_element_offset(self.h, block, kv_head, int(is_v), slot, dim))
@@ -353,7 +361,14 @@ class Pool:
         return k, v
 
 
-def sk_top2(logits, stream=None, workspace=None):
+def top2_outputs(rows, device):
+    """Output tensors of sk_top2 / sk_top2_static for `rows` rows: (idx1, idx2, val1, val2, gap)."""
+    idx1 = torch.empty(rows, dtype=torch.int32, device=device)
+    val1 = torch.empty(rows, dtype=torch.float32, device=device)
+    return idx1, torch.empty_like(idx1), val1, torch.empty_like(val1), torch.empty_like(val1)
+
+
+def sk_top2(logits, stream=None, workspace=None, outputs=None):
     """logits: CUDA float32 tensor [rows, vocab] (rows may be strided by a multiple of 4 elements).
     Returns (idx1, idx2, val1, val2, gap), each [rows]."""
     assert logits.is_cuda and logits.dtype == torch.float32 and logits.dim() == 2 and logits.stride(1) == 1
@@ -361,11 +376,7 @@ def sk_top2(logits, stream=None, workspace=None):
     need = lib().sk_top2_workspace_bytes(rows, vocab)
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=logits.device)
-    idx1 = torch.empty(rows, dtype=torch.int32, device=logits.device)
-    idx2 = torch.empty_like(idx1)
-    val1 = torch.empty(rows, dtype=torch.float32, device=logits.device)
-    val2 = torch.empty_like(val1)
-    gap = torch.empty_like(val1)
+    idx1, idx2, val1, val2, gap = outputs if outputs is not None else top2_outputs(rows, logits.device)
     _ck(lib().sk_top2(ctypes.c_void_p(logits.data_ptr()) if rows else None, rows, vocab, logits.stride(0) if rows else vocab, _p(workspace),
                       workspace.numel(), _p(idx1), _p(idx2), _p(val1), _p(val2), _p(gap), _stream(stream)), "sk_top2")
     return idx1, idx2, val1, val2, gap

@@ -60,7 +60,11 @@ struct sk_work {
     int32_t tok_period;   // > 0: the tile packs sequences of tok_period tokens each, all starting at pos0;
     int32_t sub_blocks;   // sequence k's second uncommitted segment starts at staging block eph_blk[1] + k * sub_blocks
     int32_t kv_step;      // keys from one 64-key iteration over [kv_begin, kv_end) to the next; 0 = 64 (contiguous)
-    int32_t pad;
+    // in-kernel merge of the split partials (part >= 0 and sk_launch::fuse): the workgroups of one
+    // (row tile, KV head) are a unit; its partial slots are part0, part0 + Hkv, .. (n_parts of them)
+    int32_t unit;         // index of the unit's pair of counters in sk_launch::sync
+    int32_t part0;
+    int32_t n_parts;
 };
 
 // One row tile of the cross-split combine.
@@ -95,7 +99,8 @@ struct sk_launch {
     const void* q;
     void* out;
     float* lse;
-    float* part_ml;       // [slot][rows_per_slot][2]  (running max in log2 units, sum)
+    float* part_ml;       // [slot][rows_per_slot][4]  (reference maximum in log2 units, sum of the weights as
+                          //  rounded for the matrix pipe, sum of the unrounded weights, unused)
     float* part_o;        // [slot][rows_per_slot][d]  unnormalised
     const sk_work* work;  // list mode
     const sk_comb* comb;  // list mode
@@ -111,6 +116,15 @@ struct sk_launch {
     // s + 2S, .. of the cache instead of one contiguous chunk, so that the workgroups of a head walk
     // through memory side by side instead of as S separate streams (the host decides when)
     int32_t interleave;
+    // In-kernel merge of the split partials.  sync holds two counters per unit, both zero between
+    // launches: arrivals (low 16 bits; the high bits count workgroups that gave up waiting) and
+    // departures.  A workgroup writes its partial, arrives, and waits up to wait_polls polls for the
+    // others; then every workgroup of the unit merges its own share of the rows.  One that gives up
+    // leaves its share to the last arriver, which always sees everything (no wait is unbounded).
+    // The last to leave clears the counters.
+    uint32_t* sync;
+    int32_t fuse;
+    int32_t wait_polls;
 };
 
 // Launchers implemented in sk_kernels.hip (return hipError_t as int).
@@ -124,3 +138,4 @@ int sk_launch_attention(const sk_launch& L, int variant, int32_t n_workgroups, v
 int sk_launch_combine(const sk_launch& L, int32_t n_row_tiles, void* stream);
 int sk_launch_gather(const sk_geom& g, int32_t tbl_off, int64_t first, int64_t count,
                      void* k_out, void* v_out, void* stream);
+int sk_launch_copy_block(const sk_geom& g, unsigned char* kv_rw, int32_t src, int32_t dst, void* stream);

@@ -78,6 +78,7 @@ __device__ __forceinline__ bool sk_decode_work(const sk_launch& P, int b, sk_wor
         w.kv_end = e < kv_vis ? e : kv_vis;
     }
     w.part = (P.n_splits == 1) ? -1 : (tile * P.n_splits + split) * Hkv + head;
+    w.unit = tile * Hkv + head; w.part0 = tile * P.n_splits * Hkv + head; w.n_parts = np;
     w.hole_lo = P.hole_lo; w.hole_hi = P.hole_hi;
     w.tok_period = 0; w.sub_blocks = 0;
     for (int i = 0; i < 2; ++i) {
@@ -131,6 +132,69 @@ __device__ __forceinline__ const unsigned char* sk_group_base(const sk_seg& g, i
     typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
     const int blk = ((const_i32_ptr)(uintptr_t)g.table)[tg >> g.log2B];
     return g.base + (int64_t)blk * g.blk_stride;
+}
+
+// One wave merges the split partials of one output row (partial row prow0 of the first split, the
+// others pstride rows apart):
+//   M = max_s m_s ; w_s = 2^(m_s - M) ; O = sum_s O_s w_s / sum_s l_s w_s ; LSE = (M + log2 sum_s lx_s w_s) ln 2
+// Lane s holds the statistics of split s, every lane two (d = 128) or one (d = 64) output dimensions.
+// The splits are added in index order whoever calls this (the combine kernel, or a workgroup of the
+// attention kernel), so the result depends on the partials only.  Up to 32 splits are read with one
+// memory round trip: every load is issued before the first value is used.
+__device__ __forceinline__ void sk_merge_row(const sk_launch& P, const size_t prow0, const size_t pstride, const int n_parts,
+                                             const size_t orow, const int lane)
+{
+    const int d = P.g.d;
+    const int per_lane = d >> 6;     // 1 (d=64) or 2 (d=128)
+    const float* obase = P.part_o + prow0 * d + per_lane * lane;
+    const size_t ostride = pstride * d;
+    const float4* mlbase = (const float4*)P.part_ml + prow0;
+    float M = SK_NEG_INF;
+    if (n_parts > 32) {              // rare: the maximum needs its own pass
+        for (int s = lane; s < n_parts; s += 64) M = fmaxf(M, mlbase[(size_t)s * pstride].x);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
+    }
+    float L = 0.f, Lx = 0.f, a0 = 0.f, a1 = 0.f;
+    for (int base = 0; base < n_parts; base += 32) {
+        const int cnt = n_parts - base < 32 ? n_parts - base : 32;
+        float2 x[32];
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+            x[j] = make_float2(0.f, 0.f);
+            if (j < cnt) {
+                const float* op = obase + (size_t)(base + j) * ostride;
+                if (per_lane == 2) x[j] = *(const float2*)op; else x[j].x = *op;
+            }
+        }
+        float4 ml = make_float4(SK_NEG_INF, 0.f, 0.f, 0.f);
+        if (lane < cnt) ml = mlbase[(size_t)(base + lane) * pstride];
+        if (n_parts <= 32) {
+            M = ml.x;
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
+        }
+        const float wgt = (ml.x == SK_NEG_INF) ? 0.f : sk_exp2(ml.x - M);
+        L = fmaf(ml.y, wgt, L); Lx = fmaf(ml.z, wgt, Lx);      // explicit FMAs: every copy of this function rounds alike
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+            const float wj = __shfl(wgt, j, 64);         // 0 for splits past the end
+            a0 = fmaf(x[j].x, wj, a0); a1 = fmaf(x[j].y, wj, a1);
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) { L += __shfl_xor(L, off, 64); Lx += __shfl_xor(Lx, off, 64); }
+    const float inv = 1.0f / L;
+    if (P.out_dtype == 0) {
+        float* o = (float*)P.out + orow * d;
+        if (per_lane == 2) *(float2*)(o + 2 * lane) = make_float2(a0 * inv, a1 * inv);
+        else o[lane] = a0 * inv;
+    } else {
+        uint16_t* o = (uint16_t*)P.out + orow * d;
+        if (per_lane == 2) *(uint32_t*)(o + 2 * lane) = f32_to_bf16_bits(a0 * inv) | ((uint32_t)f32_to_bf16_bits(a1 * inv) << 16);
+        else o[lane] = f32_to_bf16_bits(a0 * inv);
+    }
+    if (P.lse && lane == 0) P.lse[orow] = (M + sk_log2(Lx)) * SK_LN2;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -328,6 +392,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
 #pragma unroll
         for (int v = 0; v < 16; ++v) oacc[mt][v] = 0.f;
     float m_ref = SK_NEG_INF, l_run = 0.f;
+    float lx_run = 0.f;                  // sum of the weights before rounding: what the log-sum-exp is taken from
     const float c_scale = P.g.scale_log2e;
     // key tau(rho): swap bits 2 and 3 of the S^T row index
     const int tau = (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1);
@@ -437,7 +502,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
             const bool raise = mt_ > m_ref + SK_RESCALE_SLACK;
             if (__any(raise)) {
                 const float alpha = raise ? sk_exp2(m_ref - mt_) : 1.0f;
-                l_run *= alpha;
+                l_run *= alpha; lx_run *= alpha;
 #pragma unroll
                 for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
@@ -445,6 +510,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
                 m_ref = raise ? mt_ : m_ref;
             }
             const float neg_m = (m_ref == SK_NEG_INF) ? 0.f : -m_ref;
+            float lx0 = 0.f, lx1 = 0.f;
 #pragma unroll
             for (int t = 0; t < TPW; ++t)
 #pragma unroll
@@ -452,11 +518,15 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
                     const float p0 = sk_exp2(fmaf(sacc[t][v], c_scale, neg_m)), p1 = sk_exp2(fmaf(sacc[t][8 + v], c_scale, neg_m));
                     pb[t][0][v] = (__bf16)p0;
                     pb[t][1][v] = (__bf16)p1;
+                    lx0 += p0; lx1 += p1;
                 }
-            // The row sum is taken over the weights as the matrix pipe sees them (rounded to bf16), two
-            // per instruction with fp32 accumulation: numerator and denominator of the output then
-            // carry the same weights, so a row that one key dominates keeps that key's value to fp32
-            // accuracy whatever the rounding of its weight (with the lazy maximum that weight is not 1).
+            lx_run += lx0 + lx1;
+            // The row sum that normalises the output is taken over the weights as the matrix pipe sees
+            // them (rounded to bf16), two per instruction with fp32 accumulation: numerator and
+            // denominator of the output then carry the same weights, so a row that one key dominates
+            // keeps that key's value to fp32 accuracy whatever the rounding of its weight (with the lazy
+            // maximum that weight is not 1).  The log-sum-exp is taken from the unrounded weights
+            // (lx_run, above), so it does not carry the rounding.
             const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
             float ls0 = 0.f, ls1 = 0.f;
 #pragma unroll
@@ -692,11 +762,12 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
     }
 
     float l_tot; { const sk_halves h = sk_both_halves(l_run); l_tot = h.lo + h.hi; }
+    float lx_tot; { const sk_halves h = sk_both_halves(lx_run); lx_tot = h.lo + h.hi; }
 
     if (NPH > 1) {
-        // merge the key phases of each row group through LDS: [value index][lane], value 64 = m, 65 = l
+        // merge the key phases of each row group through LDS: [value index][lane], value 64 = m, 65 = l, 66 = lx
         __syncthreads();
-        float* xch = (float*)&lds[0] + rg * (66 * 64);
+        float* xch = (float*)&lds[0] + rg * (67 * 64);
         if (ph == 1) {
 #pragma unroll
             for (int mt = 0; mt < 4; ++mt)
@@ -704,10 +775,11 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
                 for (int v = 0; v < 16; ++v) xch[(mt * 16 + v) * 64 + lane] = oacc[mt][v];
             xch[64 * 64 + lane] = m_ref;
             xch[65 * 64 + lane] = l_tot;
+            xch[66 * 64 + lane] = lx_tot;
         }
         __syncthreads();
-        if (ph == 1) return;
-        const float m1 = xch[64 * 64 + lane], l1 = xch[65 * 64 + lane];
+        if (ph == 0) {
+        const float m1 = xch[64 * 64 + lane], l1 = xch[65 * 64 + lane], lx1 = xch[66 * 64 + lane];
         const float M = fmaxf(m_ref, m1);
         const float a0 = (m_ref == SK_NEG_INF) ? 0.f : sk_exp2(m_ref - M);
         const float a1 = (m1 == SK_NEG_INF) ? 0.f : sk_exp2(m1 - M);
@@ -716,7 +788,10 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
 #pragma unroll
             for (int v = 0; v < 16; ++v) oacc[mt][v] = oacc[mt][v] * a0 + xch[(mt * 16 + v) * 64 + lane] * a1;
         l_tot = l_tot * a0 + l1 * a1;
+        lx_tot = lx_tot * a0 + lx1 * a1;
         m_ref = M;
+        }
+        __syncthreads();                                  // the exchange area is read; the transposes below reuse it
     }
 
     // ---- epilogue: rows go out through LDS so that every store instruction writes whole rows ----
@@ -726,7 +801,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
     // ring holds one such tile per wave: 64 KiB for four waves, 128 KiB for eight).
     if (NPH == 1) __syncthreads();                    // every wave is done reading key tiles
     const bool direct = w.part < 0;
-    auto emit = [&]() __attribute__((always_inline)) {
+    if (NPH == 1 || ph == 0) {                        // with two key phases, phase 0 holds the merged rows
         const float inv = direct ? 1.0f / l_tot : 1.0f;
         float* tr = (float*)lds + (NPH == 1 ? wave : rg * 2) * 4096;
 #pragma unroll
@@ -739,8 +814,8 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
             }
         const size_t orow_lane = ((size_t)(w.q_tok0 + tok_local) * P.g.Hq + hq);
         if (row_valid && kg == 0) {
-            if (direct) { if (P.lse) P.lse[orow_lane] = (m_ref + sk_log2(l_tot)) * SK_LN2; }
-            else *(float2*)(P.part_ml + ((size_t)w.part * P.rows_per_slot + row_in_tile) * 2) = make_float2(m_ref, l_tot);
+            if (direct) { if (P.lse) P.lse[orow_lane] = (m_ref + sk_log2(lx_tot)) * SK_LN2; }
+            else *((float4*)P.part_ml + ((size_t)w.part * P.rows_per_slot + row_in_tile)) = make_float4(m_ref, l_tot, lx_tot, 0.f);
         }
         const int c4 = lane & 31;
 #pragma unroll
@@ -765,8 +840,65 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
                 *(float4*)(P.part_o + ((size_t)w.part * P.rows_per_slot + rit) * 128 + c4 * 4) = val;
             }
         }
-    };
-    emit();
+    }
+    if (direct || !P.fuse) return;
+
+    // ---- in-kernel merge of the split partials ----
+    // The workgroups of one (row tile, KV head) are a unit.  Each has written its partial above; it
+    // now arrives at the unit's counter and waits, for a bounded number of polls, until all have
+    // arrived; then every workgroup of the unit merges its own share of the tile's rows (split k the
+    // rows k * rps ..), reading the other partials through the L2.  A workgroup that gives up waiting
+    // says so in the counter's high bits and leaves; the last workgroup to arrive (which never waits,
+    // so the scheme needs no two workgroups to be resident together) then merges every share.  Who
+    // merges a row does not change its value: sk_merge_row adds the splits in index order.
+    __syncthreads();                                  // the whole partial is written (and LDS is free again)
+    volatile int* flag = (volatile int*)lds;
+    uint32_t* cnt = P.sync + 2 * (size_t)w.unit;
+    if (tid == 0) {
+        __threadfence();                              // release: the partial is visible device-wide before the arrival
+        const uint32_t np = (uint32_t)w.n_parts;
+        const uint32_t old = __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int state;                                    // 0: leave, 1: merge the own share, 2: merge every share
+        if ((old & 0xffffu) + 1u == np) state = (old >> 16) ? 2 : 1;
+        else {
+            state = 0;
+            for (int i = 0; i < P.wait_polls; ++i) {
+                __builtin_amdgcn_s_sleep(8);
+                if ((__hip_atomic_load(cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & 0xffffu) == np) { state = 1; break; }
+            }
+            if (state == 0) {
+                // gave up.  The mark and the last arrival are atomic operations on one word: either the last
+                // arriver sees the mark (and merges this share), or this sees that everybody has arrived.
+                const uint32_t o2 = __hip_atomic_fetch_add(cnt, 0x10000u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if ((o2 & 0xffffu) == np) state = 1;
+            }
+        }
+        __threadfence();                              // acquire: the other partials are read after the counter
+        *flag = state;
+    }
+    __syncthreads();
+    const int state = *flag;
+    if (state != 0) {
+        const int nrows = w.n_tok * G;
+        const int rps = (nrows + w.n_parts - 1) / w.n_parts;
+        const int k_own = (w.part - w.part0) / P.g.Hkv;
+        const int k_lo = state == 2 ? 0 : k_own, k_hi = state == 2 ? w.n_parts : k_own + 1;
+        for (int k = k_lo; k < k_hi; ++k) {
+            const int row_end = (k + 1) * rps < nrows ? (k + 1) * rps : nrows;
+            for (int row = k * rps + wave; row < row_end; row += NW) {
+                const size_t orow = (size_t)(w.q_tok0 + (row >> log2G)) * P.g.Hq + w.kv_head * G + (row & (G - 1));
+                sk_merge_row(P, (size_t)w.part0 * P.rows_per_slot + row, (size_t)P.g.Hkv * P.rows_per_slot, w.n_parts, orow, lane);
+            }
+        }
+    }
+    // departure: the last workgroup of the unit to get here clears the counters for the next launch
+    if (tid == 0) {
+        const uint32_t left = __hip_atomic_fetch_add(cnt + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (left + 1u == (uint32_t)w.n_parts) {
+            __hip_atomic_store(cnt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(cnt + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -894,13 +1026,14 @@ __global__ __launch_bounds__(256) void sk_attn_simple(const sk_launch P)
 #pragma unroll
         for (int j = 0; j < 8; ++j)
             if (j < nd) P.part_o[prow * d + c + 16 * j] = o[j];
-        if (c == 0) { P.part_ml[prow * 2] = m_run; P.part_ml[prow * 2 + 1] = l_run; }
+        if (c == 0) *((float4*)P.part_ml + prow) = make_float4(m_run, l_run, l_run, 0.f);
     }
 }
 
 // ---------------------------------------------------------------------------------------------
 // Cross-split combine: one wave per output row.
-//   M = max_s m_s ; L = sum_s l_s 2^(m_s - M) ; O = sum_s O_s 2^(m_s - M) / L ; LSE = (M + log2 L) ln 2
+//   M = max_s m_s ; L = sum_s l_s 2^(m_s - M) ; O = sum_s O_s 2^(m_s - M) / L
+//   LSE = (M + log2 sum_s lx_s 2^(m_s - M)) ln 2       (lx: the row sums before bf16 rounding)
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void sk_combine(const sk_launch P)
 {
@@ -920,76 +1053,10 @@ __global__ __launch_bounds__(256) void sk_combine(const sk_launch P)
         cb.part0 = tile * P.n_splits * Hkv + head; cb.part_stride = Hkv;
         cb.q_tok0 = tok0; cb.n_tok = ntok; cb.kv_head = head;
     }
-    const int G = P.g.G, d = P.g.d;
+    const int G = P.g.G;
     if (row >= cb.n_tok * G) return;
-    const int tok_local = row / G;
-    const int hq = cb.kv_head * G + row % G;
-    const size_t prow0 = (size_t)cb.part0 * P.rows_per_slot + row;
-    const size_t pstride = (size_t)cb.part_stride * P.rows_per_slot;
-    // Lane s owns (m, l) of part base+s; rows are read in batches of eight parts, the next
-    // batch requested before the current one is used, so one memory latency covers the kernel.
-    const int per_lane = d >> 6;     // 1 (d=64) or 2 (d=128)
-    const float* obase = P.part_o + prow0 * d + per_lane * lane;
-    const size_t ostride = pstride * d;
-    float M = SK_NEG_INF;
-    if (cb.n_parts > 64) {           // rare: the maximum needs its own pass
-        for (int s = lane; s < cb.n_parts; s += 64) M = fmaxf(M, P.part_ml[(prow0 + s * pstride) * 2]);
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
-    }
-    float L = 0.f, a0 = 0.f, a1 = 0.f;
-    for (int base = 0; base < cb.n_parts; base += 64) {
-        const int cnt = cb.n_parts - base < 64 ? cb.n_parts - base : 64;
-        float2 ml = make_float2(SK_NEG_INF, 0.f);
-        if (lane < cnt) ml = *(const float2*)(P.part_ml + (prow0 + (base + lane) * pstride) * 2);
-        float2 x[8], y[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            x[j] = make_float2(0.f, 0.f);
-            if (j < cnt) {
-                const float* op = obase + (size_t)(base + j) * ostride;
-                if (per_lane == 2) x[j] = *(const float2*)op; else x[j].x = *op;
-            }
-        }
-        if (cb.n_parts <= 64) {
-            M = ml.x;
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
-        }
-        const float wgt = (ml.x == SK_NEG_INF) ? 0.f : sk_exp2(ml.x - M);
-        L += ml.y * wgt;
-        for (int j0 = 0; j0 < cnt; j0 += 8) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {           // request the next batch
-                y[j] = make_float2(0.f, 0.f);
-                if (j0 + 8 + j < cnt) {
-                    const float* op = obase + (size_t)(base + j0 + 8 + j) * ostride;
-                    if (per_lane == 2) y[j] = *(const float2*)op; else y[j].x = *op;
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const float wj = __shfl(wgt, j0 + j, 64);    // 0 for parts past the end
-                a0 += x[j].x * wj; a1 += x[j].y * wj;
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) x[j] = y[j];
-        }
-    }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) L += __shfl_xor(L, off, 64);
-    const float inv = 1.0f / L;
-    const size_t orow = ((size_t)(cb.q_tok0 + tok_local) * P.g.Hq + hq);
-    if (P.out_dtype == 0) {
-        float* o = (float*)P.out + orow * d;
-        if (per_lane == 2) *(float2*)(o + 2 * lane) = make_float2(a0 * inv, a1 * inv);
-        else o[lane] = a0 * inv;
-    } else {
-        uint16_t* o = (uint16_t*)P.out + orow * d;
-        if (per_lane == 2) *(uint32_t*)(o + 2 * lane) = f32_to_bf16_bits(a0 * inv) | ((uint32_t)f32_to_bf16_bits(a1 * inv) << 16);
-        else o[lane] = f32_to_bf16_bits(a0 * inv);
-    }
-    if (P.lse && lane == 0) P.lse[orow] = (M + sk_log2(L)) * SK_LN2;
+    const size_t orow = ((size_t)(cb.q_tok0 + row / G) * P.g.Hq + cb.kv_head * G + row % G);
+    sk_merge_row(P, (size_t)cb.part0 * P.rows_per_slot + row, (size_t)cb.part_stride * P.rows_per_slot, cb.n_parts, orow, lane);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1096,6 +1163,18 @@ __global__ __launch_bounds__(256) void sk_gather_kernel(const sk_geom g, int32_t
     }
 }
 
+// Copies pool block `src` to block `dst`, all KV heads (the one block a fork or a copy-on-write
+// duplicates).  Offsets are formed in 64 bits: a head's blocks lie head_stride bytes apart, which
+// exceeds 2 GiB in large pools.
+__global__ __launch_bounds__(256) void sk_copy_block_kernel(const sk_geom g, unsigned char* kv_rw, int32_t src, int32_t dst)
+{
+    const int head = blockIdx.y;
+    const int64_t n16 = g.blk_stride >> 4;
+    const uint4* s4 = (const uint4*)(kv_rw + (int64_t)head * g.head_stride + (int64_t)src * g.blk_stride);
+    uint4* d4 = (uint4*)(kv_rw + (int64_t)head * g.head_stride + (int64_t)dst * g.blk_stride);
+    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n16; i += (int64_t)gridDim.x * blockDim.x) d4[i] = s4[i];
+}
+
 // ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
@@ -1150,5 +1229,14 @@ int sk_launch_gather(const sk_geom& g, int32_t tbl_off, int64_t first, int64_t c
     if (blocks > 65535) blocks = 65535;
     hipLaunchKernelGGL(sk_gather_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
                        g, tbl_off, first, count, k_out, v_out);
+    return (int)hipGetLastError();
+}
+
+int sk_launch_copy_block(const sk_geom& g, unsigned char* kv_rw, int32_t src, int32_t dst, void* stream)
+{
+    const int64_t n16 = g.blk_stride >> 4;
+    int64_t bx = (n16 + 255) / 256;
+    if (bx > 64) bx = 64;
+    hipLaunchKernelGGL(sk_copy_block_kernel, dim3((unsigned)bx, (unsigned)g.Hkv), dim3(256), 0, (hipStream_t)stream, g, kv_rw, src, dst);
     return (int)hipGetLastError();
 }

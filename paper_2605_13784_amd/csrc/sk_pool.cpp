@@ -18,9 +18,10 @@ namespace {
 thread_local int g_last_hip = 0;
 
 constexpr int kRingSlots = 4;
-constexpr size_t kMetaBytes = 4u << 20;          // device region for uploaded lists (and ring slot size)
+constexpr size_t kMinMetaBytes = 4u << 20;       // least size of the device region for uploaded lists (= ring slot size)
 constexpr int kPartSlotRows = 128;               // rows reserved per partial slot
 constexpr int kDefaultTargetWgs = 512;
+constexpr int kDefaultWaitPolls = 256;           // polls a workgroup waits for the others of its unit (about 1 us each)
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int ilog2_exact(int64_t x) { int l = 0; while ((int64_t(1) << l) < x) ++l; return ((int64_t(1) << l) == x) ? l : -1; }
@@ -46,9 +47,11 @@ struct Layout {
     int32_t max_batch_tokens = 0;
     int64_t eph_blocks = 0;
     int64_t part_slots = 0;
+    int64_t sync_units = 0;           // pairs of merge counters
+    size_t meta_bytes = 0;            // device region for uploaded lists; also the size of a pinned ring slot
     size_t kv_bytes = 0;
     // workspace offsets
-    size_t off_tables = 0, off_ident = 0, off_meta = 0, off_part_ml = 0, off_part_o = 0, off_eph = 0, ws_bytes = 0;
+    size_t off_tables = 0, off_ident = 0, off_meta = 0, off_sync = 0, off_part_ml = 0, off_part_o = 0, off_eph = 0, ws_bytes = 0;
 };
 
 bool derive_layout(const sk_pool_desc& d, Layout& L)
@@ -71,12 +74,27 @@ bool derive_layout(const sk_pool_desc& d, Layout& L)
     L.eph_head_stride = 0;     // set once the number of staging blocks is known
     int64_t mst = d.max_session_tokens ? d.max_session_tokens : d.n_blocks * d.block_tokens;
     mst = std::min<int64_t>(mst, d.n_blocks * d.block_tokens);
-    mst = std::min<int64_t>(mst, int64_t(kMetaBytes / 4) * d.block_tokens);    // a session's block table is uploaded in one piece
+    mst = std::min<int64_t>(mst, int64_t(kMinMetaBytes / 4) * d.block_tokens);    // a session's block table is uploaded in one piece
     if (mst > (int64_t(1) << 29)) return false;       // positions are int32 with head room
     L.max_session_tokens = mst;
     L.max_blocks_per_session = (mst + d.block_tokens - 1) / d.block_tokens;
+    // offsets into the device block tables are 32-bit
+    if (int64_t(d.max_sessions) * L.max_blocks_per_session >= (int64_t(1) << 31)) return false;
     L.max_batch_tokens = d.max_batch_tokens ? d.max_batch_tokens : 4096;
     if (L.max_batch_tokens > (1 << 20)) return false;
+    {   // The lists a batched call uploads always fit when every row tile is one workgroup per KV head
+        // (the planner falls back to that): a call has at most max_batch_tokens tokens in at most
+        // min(max_sessions, max_batch_tokens) items (question batches: one tile per question at worst),
+        // so at most tiles_max row tiles and scat_max 16-token scatter groups.
+        const int64_t items_max = std::min<int64_t>(std::max(d.max_sessions, 1024), L.max_batch_tokens);
+        const int64_t tpt_min = std::max(1, 16 / L.G);                          // tokens per row tile of the smallest kernel
+        const int64_t tiles_max = L.max_batch_tokens / tpt_min + items_max;
+        const int64_t scat_max = L.max_batch_tokens / 16 + 2 * items_max + 2;
+        const int64_t need = tiles_max * d.n_kv_heads * int64_t(sizeof(sk_work) + sizeof(sk_comb)) + scat_max * int64_t(sizeof(sk_scatter)) + 16 * 256;
+        // Capped at 64 MiB: a step whose lists do not fit even then is refused with SK_E_WORKSPACE and
+        // leaves every session as it was.
+        L.meta_bytes = align_up(std::max<size_t>(kMinMetaBytes, std::min<size_t>(size_t(need), size_t(64) << 20)), 256);
+    }
     L.eph_blocks = (L.max_batch_tokens + 15) / 16 + std::max(d.max_sessions, 1024) + 1;
     L.eph_head_stride = L.eph_blk_stride * L.eph_blocks;
     int64_t rows = int64_t(L.max_batch_tokens) * d.n_q_heads;
@@ -85,8 +103,12 @@ bool derive_layout(const sk_pool_desc& d, Layout& L)
     size_t off = 0;
     L.off_tables = off; off = align_up(off + size_t(d.max_sessions) * L.max_blocks_per_session * 4, 256);
     L.off_ident = off;  off = align_up(off + size_t(L.eph_blocks) * 4, 256);
-    L.off_meta = off;   off = align_up(off + kMetaBytes, 256);
-    L.off_part_ml = off; off = align_up(off + size_t(L.part_slots) * kPartSlotRows * 2 * 4, 256);
+    L.off_meta = off;   off = align_up(off + L.meta_bytes, 256);
+    // one unit of merge counters per (row tile, KV head) of a call; the matrix-pipe kernels, which merge
+    // in the kernel, have tiles of at least 64 rows
+    L.sync_units = (rows / 64 + std::max(d.max_sessions, 1024) + 2) * d.n_kv_heads;
+    L.off_sync = off;   off = align_up(off + size_t(L.sync_units) * 8, 256);
+    L.off_part_ml = off; off = align_up(off + size_t(L.part_slots) * kPartSlotRows * 4 * 4, 256);
     L.off_part_o = off; off = align_up(off + size_t(L.part_slots) * kPartSlotRows * d.head_dim * 4, 256);
     L.off_eph = off;    off = align_up(off + size_t(L.eph_blocks) * L.eph_blk_stride * d.n_kv_heads, 256);
     L.ws_bytes = off;
@@ -116,6 +138,12 @@ struct sk_pool {
     int target_wgs = kDefaultTargetWgs;
     bool target_wgs_set = false;
     bool force_simple = false, no_256 = false, no_pack = false, no_interleave = false;
+    bool fuse = true;                    // single-session calls merge their split partials inside the attention kernel
+    bool fuse_list = false;              // batched calls too (the last workgroup of a unit merges alone)
+    int wait_polls = kDefaultWaitPolls;
+    int n_cus = 256;                     // compute units of the device the pool was created on
+    // test hook (sk_pool_inject_failure): the countdown-th arrival at `inject_site` fails
+    int inject_site = 0, inject_countdown = 0;
     // optional kernel timing
     bool profiling = false;
     std::vector<hipEvent_t> prof_ev;     // triples: before attention, after attention, after combine
@@ -145,24 +173,47 @@ int64_t blocks_needed(const sk_pool* p, int64_t len, int64_t add)
     return (len + add + B - 1) / B - (len + B - 1) / B;
 }
 
-// Takes a ring slot (waiting for the copy that last used it), returns its host pointer.
+// Test hook: true when a failure was ordered for this site and its countdown has run out.  The sites
+// are visited in the same order by device pools and by metadata-only pools (which skip the HIP call
+// itself), so the error paths behind them can be exercised without a GPU.
+bool inject(sk_pool* p, int site)
+{
+    if (p->inject_site != site || p->inject_site == 0) return false;
+    if (--p->inject_countdown > 0) return false;
+    p->inject_site = 0;
+    g_last_hip = (int)hipErrorUnknown;
+    return true;
+}
+
+// Takes a ring slot (waiting for the copy that last used it), returns its host pointer (null for a
+// metadata-only pool).  Changes nothing when it fails.
 int ring_acquire(sk_pool* p, int* slot, unsigned char** host)
 {
+    if (inject(p, SK_SITE_RING)) return SK_E_HIP;
+    *slot = 0; *host = nullptr;
+    if (!p->device) return SK_OK;
     int s = p->ring_next;
-    p->ring_next = (s + 1) % kRingSlots;
     if (p->ring_used[s]) SK_HIP(hipEventSynchronize(p->ring_ev[s]));
+    p->ring_next = (s + 1) % kRingSlots;
     *slot = s;
-    *host = p->ring + size_t(s) * kMetaBytes;
+    *host = p->ring + size_t(s) * p->L.meta_bytes;
+    return SK_OK;
+}
+
+// Copies `bytes` from ring slot `slot` to `dev` on the stream and marks the slot busy until then.
+int ring_copy(sk_pool* p, int slot, void* dev, size_t bytes, hipStream_t st)
+{
+    if (inject(p, SK_SITE_UPLOAD)) return SK_E_HIP;
+    if (!p->device) return SK_OK;
+    SK_HIP(hipMemcpyAsync(dev, p->ring + size_t(slot) * p->L.meta_bytes, bytes, hipMemcpyHostToDevice, st));
+    if (hipEventRecord(p->ring_ev[slot], st) != hipSuccess) (void)hipStreamSynchronize(st);   // the slot is free either way
+    p->ring_used[slot] = true;
     return SK_OK;
 }
 
 int ring_upload(sk_pool* p, int slot, size_t bytes, hipStream_t st)
 {
-    unsigned char* dev = (unsigned char*)p->d.workspace + p->L.off_meta;
-    SK_HIP(hipMemcpyAsync(dev, p->ring + size_t(slot) * kMetaBytes, bytes, hipMemcpyHostToDevice, st));
-    SK_HIP(hipEventRecord(p->ring_ev[slot], st));
-    p->ring_used[slot] = true;
-    return SK_OK;
+    return ring_copy(p, slot, p->device ? (unsigned char*)p->d.workspace + p->L.off_meta : nullptr, bytes, st);
 }
 
 // With profiling on, reserves three events for this call and records the first.
@@ -208,20 +259,30 @@ void fill_launch_common(const sk_pool* p, sk_launch& L, const void* q, void* out
     unsigned char* ws = (unsigned char*)p->d.workspace;
     L.part_ml = (float*)(ws + p->L.off_part_ml);
     L.part_o = (float*)(ws + p->L.off_part_o);
+    L.sync = (uint32_t*)(ws + p->L.off_sync);
     L.out_dtype = out_dtype == SK_F32 ? 0 : 1;
     L.rows_per_slot = v.rows_per_slot;
 }
 
 // Regular-mode attention over one session: n_tok new tokens at positions pos0.. (or no causal
 // limit), kv_len cached tokens, optionally one uncommitted segment already in staging block 0.
-int run_regular(sk_pool* p, int32_t id, const void* q, int64_t n_tok, int32_t pos0, int64_t kv_len,
-                int32_t eph_cnt, int32_t eph_pos0, void* out, int out_dtype, float* lse,
-                int32_t n_splits_req, hipStream_t st)
-{
+// plan_regular decides the decomposition and is the only part that can refuse the call (it reads
+// nothing but sizes, so it runs before a call changes anything); launch_regular enqueues it.
+struct RegPlan {
     Variant v;
+    sk_launch L;           // everything but the pointers
+    int32_t wgs = 0, base_wgs = 0, parts = 1;
+    int64_t kv_len = 0;
+};
+
+int plan_regular(const sk_pool* p, int32_t id, int64_t n_tok, int32_t pos0, int64_t kv_len, int32_t eph_cnt, int32_t eph_pos0,
+                 int64_t hole_lo, int64_t hole_hi, int32_t n_splits_req, RegPlan& R)
+{
+    Variant& v = R.v;
     if (!pick_variant(p, n_tok, v, !p->no_256)) return SK_E_SHAPE;
-    sk_launch L;
-    fill_launch_common(p, L, q, out, out_dtype, lse, v);
+    sk_launch& L = R.L;
+    memset(&L, 0, sizeof L);
+    L.rows_per_slot = v.rows_per_slot;
     L.mode = SK_MODE_REGULAR;
     L.tbl_off = int32_t(int64_t(id) * p->L.max_blocks_per_session);
     L.n_tok = (int32_t)n_tok;
@@ -254,29 +315,54 @@ int run_regular(sk_pool* p, int32_t id, const void* q, int64_t n_tok, int32_t po
         if (S <= 1) break;
     }
     if (parts > 1 && base_wgs * parts * v.rows_per_slot > slots_rows) return SK_E_WORKSPACE;
+    if (base_wgs * parts > (int64_t(1) << 30)) return SK_E_WORKSPACE;
     L.chunk = (int32_t)chunk;
     L.n_splits = (int32_t)parts;
     L.eph_blk[0] = 0; L.eph_cnt[0] = eph_cnt; L.eph_pos0[0] = eph_pos0;
-    L.hole_lo = (int32_t)p->sessions[id].frozen; L.hole_hi = (int32_t)p->sessions[id].win;
+    L.hole_lo = (int32_t)hole_lo; L.hole_hi = (int32_t)hole_hi;
     // Small queries (at most 64 rows per KV head; every cached token visible to every row): the splits
     // interleave their 64-key pieces.  Measured 3-5 % faster there (16 tokens at 128K: 99.5 -> 96 us),
     // 2-3 % slower for the 128-row instance, which keeps contiguous chunks.  Larger blocks gain more
     // (16 tokens at 128K: 98 / 96 / 92 us with 16- / 64- / 256-token blocks).
     L.interleave = (!p->no_interleave && v.id == SK_KV_MFMA64 && S > 1 && kv_len <= (int64_t)pos0) ? 1 : 0;
-    const int32_t wgs = int32_t(base_wgs * parts);
+    R.base_wgs = (int32_t)base_wgs; R.parts = (int32_t)parts; R.wgs = int32_t(base_wgs * parts); R.kv_len = kv_len;
+    // The matrix-pipe kernels merge their split partials themselves (one launch per call).  Workgroups
+    // only wait for each other when the whole launch fits on the device at once (the 256-row instance
+    // holds a CU alone, the others share it in pairs); otherwise the last workgroup of a unit merges alone.
+    const bool mfma = v.id != SK_KV_SIMPLE;
+    L.fuse = (p->fuse && mfma && parts > 1 && base_wgs <= p->L.sync_units && parts < 65536) ? 1 : 0;
+    const int64_t resident = int64_t(p->n_cus) * (v.id == SK_KV_MFMA256 ? 1 : 2);
+    L.wait_polls = (L.fuse && R.wgs <= resident) ? p->wait_polls : 0;
+    return SK_OK;
+}
+
+// Enqueues a planned call.
+int launch_regular(sk_pool* p, RegPlan& R, const void* q, void* out, int out_dtype, float* lse, hipStream_t st)
+{
+    if (inject(p, SK_SITE_ATTENTION)) return SK_E_HIP;
+    if (!p->device) return SK_OK;
+    sk_launch L;
+    fill_launch_common(p, L, q, out, out_dtype, lse, R.v);
+    {   // the plan holds everything but the pointers
+        sk_launch& S = R.L;
+        S.g = L.g; S.q = L.q; S.out = L.out; S.lse = L.lse; S.part_ml = L.part_ml; S.part_o = L.part_o; S.sync = L.sync;
+        S.out_dtype = L.out_dtype;
+    }
     hipEvent_t* pe = prof_begin(p, st);
-    int e = sk_launch_attention(L, v.id, wgs, st);
+    int e = sk_launch_attention(R.L, R.v.id, R.wgs, st);
     if (e) { g_last_hip = e; return SK_E_HIP; }
     p->stats.launches++;
     if (pe) (void)hipEventRecord(pe[1], st);
-    if (parts > 1) {
-        e = sk_launch_combine(L, (int32_t)base_wgs, st);
+    if (R.parts > 1 && !R.L.fuse) {
+        // the attention kernel is enqueued and will write its partials; a failure here leaves out/lse unwritten
+        e = inject(p, SK_SITE_COMBINE) ? (int)hipErrorUnknown : sk_launch_combine(R.L, R.base_wgs, st);
         if (e) { g_last_hip = e; return SK_E_HIP; }
         p->stats.launches++;
     }
     if (pe) (void)hipEventRecord(pe[2], st);
-    p->stats.kv_bytes_streamed += kv_len * 2 * p->d.n_kv_heads * p->d.head_dim * p->L.elem * L.n_tiles;
-    p->last.workgroups = wgs; p->last.n_splits = (int32_t)parts; p->last.row_tiles = L.n_tiles; p->last.kernel_variant = v.id;
+    p->stats.kv_bytes_streamed += R.kv_len * 2 * p->d.n_kv_heads * p->d.head_dim * p->L.elem * R.L.n_tiles;
+    p->last.workgroups = R.wgs; p->last.n_splits = R.parts; p->last.row_tiles = R.L.n_tiles; p->last.kernel_variant = R.v.id;
+    p->last.fused_merge = R.L.fuse;
     return SK_OK;
 }
 
@@ -309,28 +395,46 @@ int build_scatter(const sk_pool* p, const Session* s, int32_t id, int64_t dst_to
     return SK_OK;
 }
 
-int upload_and_scatter(sk_pool* p, const std::vector<sk_scatter>& items, const void* k, const void* v, hipStream_t st)
+// A single-session scatter in two halves, so that everything that can refuse the call happens before
+// the call changes anything: scatter_reserve (size check, and a pinned ring slot if the list is too
+// long to travel in the kernel arguments), then, once the list is built, scatter_launch.
+struct ScatterSlot { bool upload = false; int slot = 0; unsigned char* host = nullptr; };
+
+int64_t scatter_groups(int64_t dst_tok0, int64_t count)     // 16-token groups the tokens dst_tok0 .. +count-1 touch
+{
+    return count <= 0 ? 0 : (dst_tok0 + count + 15) / 16 - dst_tok0 / 16;
+}
+
+int scatter_reserve(sk_pool* p, int64_t n_items, ScatterSlot& ss)
+{
+    ss = ScatterSlot();
+    if (n_items <= SK_SCATTER_ARGS_MAX) return SK_OK;
+    if (size_t(n_items) * sizeof(sk_scatter) > p->L.meta_bytes) return SK_E_WORKSPACE;
+    ss.upload = true;
+    return ring_acquire(p, &ss.slot, &ss.host);
+}
+
+int scatter_launch(sk_pool* p, const ScatterSlot& ss, const std::vector<sk_scatter>& items, const void* k, const void* v, hipStream_t st)
 {
     if (items.empty()) return SK_OK;
-    unsigned char* ws0 = (unsigned char*)p->d.workspace;
-    if (items.size() <= SK_SCATTER_ARGS_MAX) {          // short list: in the kernel arguments, nothing to upload
+    unsigned char* ws = (unsigned char*)p->d.workspace;
+    if (!ss.upload) {          // short list: in the kernel arguments, nothing to upload
+        if (inject(p, SK_SITE_SCATTER)) return SK_E_HIP;
+        if (!p->device) return SK_OK;
         sk_scatter_list lst;
         memcpy(lst.item, items.data(), items.size() * sizeof(sk_scatter));
-        int e = sk_launch_scatter_args(p->geom, k, v, lst, (int32_t)items.size(), (int32_t*)(ws0 + p->L.off_tables),
-                                       (unsigned char*)p->d.kv_mem, ws0 + p->L.off_eph, st);
+        int e = sk_launch_scatter_args(p->geom, k, v, lst, (int32_t)items.size(), (int32_t*)(ws + p->L.off_tables),
+                                       (unsigned char*)p->d.kv_mem, ws + p->L.off_eph, st);
         if (e) { g_last_hip = e; return SK_E_HIP; }
         p->stats.launches++;
         return SK_OK;
     }
     const size_t bytes = items.size() * sizeof(sk_scatter);
-    if (bytes > kMetaBytes) return SK_E_WORKSPACE;
-    int slot; unsigned char* host;
-    int rc = ring_acquire(p, &slot, &host);
+    if (ss.host) memcpy(ss.host, items.data(), bytes);
+    int rc = ring_upload(p, ss.slot, bytes, st);
     if (rc) return rc;
-    memcpy(host, items.data(), bytes);
-    rc = ring_upload(p, slot, bytes, st);
-    if (rc) return rc;
-    unsigned char* ws = (unsigned char*)p->d.workspace;
+    if (inject(p, SK_SITE_SCATTER)) return SK_E_HIP;
+    if (!p->device) return SK_OK;
     int e = sk_launch_scatter(p->geom, k, v, (const sk_scatter*)(ws + p->L.off_meta), (int32_t)items.size(),
                               (int32_t*)(ws + p->L.off_tables), (unsigned char*)p->d.kv_mem, ws + p->L.off_eph, st);
     if (e) { g_last_hip = e; return SK_E_HIP; }
@@ -363,22 +467,71 @@ bool tail_shared(const sk_pool* p, const Session* s)
     return s->len % p->d.block_tokens != 0 && p->refcnt[(size_t)s->blocks.back()] > 1;
 }
 
+// What an append changed in one session, so that a later failure of the same call can take it back.
+struct Undo {
+    Session* s = nullptr;
+    int64_t len = 0;
+    size_t n_blocks = 0;
+    int32_t old_tail = -1;       // >= 0: the shared tail block that was swapped for a copy
+};
+
 // The caller has checked that a block is free.  The copy is ordered on `st` in front of the
 // scatter that follows; the scatter also rewrites the table entry (it is told that the block is new).
-int unshare_tail(sk_pool* p, Session* s, hipStream_t st)
+// On failure nothing has changed.
+int unshare_tail(sk_pool* p, Session* s, Undo& u, hipStream_t st)
 {
     const int32_t old = s->blocks.back();
     const int32_t blk = p->free_blocks.front();
+    if (inject(p, SK_SITE_BLOCK_COPY)) return SK_E_HIP;
+    if (p->device) {
+        int e = sk_launch_copy_block(p->geom, (unsigned char*)p->d.kv_mem, old, blk, st);
+        if (e) { g_last_hip = e; return SK_E_HIP; }
+    }
     p->free_blocks.pop_front();
     p->refcnt[(size_t)blk] = 1;
     p->refcnt[(size_t)old]--;                 // still held by the others
     p->blocks_in_use++;
     s->blocks.back() = blk;
-    if (!p->device) return SK_OK;
-    unsigned char* kv = (unsigned char*)p->d.kv_mem;
-    SK_HIP(hipMemcpy2DAsync(kv + int64_t(blk) * p->L.blk_stride, (size_t)p->L.head_stride,
-                            kv + int64_t(old) * p->L.blk_stride, (size_t)p->L.head_stride,
-                            (size_t)p->L.blk_stride, (size_t)p->d.n_kv_heads, hipMemcpyDeviceToDevice, st));
+    u.old_tail = old;
+    return SK_OK;
+}
+
+// Takes an append back: the blocks it took return to the head of the free list in their old order,
+// the length is restored; the copy of a shared tail is given up too unless `keep_copy` (the commit
+// kernel is already enqueued and has pointed the device block table at the copy; keeping it changes
+// nothing a caller can observe but the number of free blocks).
+void rollback(sk_pool* p, const Undo& u, bool keep_copy)
+{
+    Session* s = u.s;
+    while (s->blocks.size() > u.n_blocks) {
+        const int32_t b = s->blocks.back();
+        s->blocks.pop_back();
+        p->refcnt[(size_t)b] = 0;
+        p->free_blocks.push_front(b);
+        p->blocks_in_use--;
+    }
+    if (u.old_tail >= 0 && !keep_copy) {
+        const int32_t blk = s->blocks.back();
+        s->blocks.back() = u.old_tail;
+        p->refcnt[(size_t)u.old_tail]++;
+        p->refcnt[(size_t)blk] = 0;
+        p->free_blocks.push_front(blk);
+        p->blocks_in_use--;
+    }
+    s->len = u.len;
+}
+
+// The host half of an append of T tokens to session s (availability already checked): copy of a
+// shared tail, new blocks, new length.  Fills `u`; on failure nothing has changed.
+int grow_session(sk_pool* p, Session* s, int64_t T, Undo& u, int64_t* first_new, hipStream_t st)
+{
+    u = Undo();
+    u.s = s; u.len = s->len; u.n_blocks = s->blocks.size();
+    const bool unshare = tail_shared(p, s);
+    if (unshare) { int rc = unshare_tail(p, s, u, st); if (rc) return rc; }
+    *first_new = (int64_t)s->blocks.size() - (unshare ? 1 : 0);
+    take_blocks(p, s, blocks_needed(p, s->len, T));
+    s->len += T;
     return SK_OK;
 }
 
@@ -422,15 +575,30 @@ void add_tiles(ListGroup& g, const TileReq& base, int32_t q_row0, int32_t T)
 
 constexpr int kMaxGroups = 3;   // one launch per kernel variant in use
 
-int run_list(sk_pool* p, ScatterBatch* sb, int n_sb, ListGroup* groups, int n_groups, int out_dtype, hipStream_t st)
+// A batched call in two halves.  plan_list cuts the tiles into workgroups, builds the lists and takes
+// the pinned ring slot they travel in: everything that can refuse the call, and nothing that changes
+// a session or the device.  launch_list uploads the lists and enqueues the kernels.
+struct ListPlan {
+    std::vector<sk_work> work[kMaxGroups];
+    std::vector<sk_comb> comb[kMaxGroups];
+    int64_t rows_base[kMaxGroups] = {};
+    int64_t kv_total = 0, n_tiles = 0;
+    bool fuse = false;
+    int slot = 0;
+    unsigned char* host = nullptr;
+    bool scatter_enqueued = false;     // set by launch_list once a commit kernel is on the stream
+};
+
+int plan_list(sk_pool* p, const ScatterBatch* sb, int n_sb, ListGroup* groups, int n_groups, ListPlan& P)
 {
     if (n_groups > kMaxGroups) return SK_E_INVAL;
+    if (inject(p, SK_SITE_PLAN)) return SK_E_WORKSPACE;
     const int Hkv = p->d.n_kv_heads;
-    int64_t kv_total = 0, n_tiles = 0;
     int64_t kv_group[kMaxGroups] = {};
+    P.kv_total = 0; P.n_tiles = 0;
     for (int gi = 0; gi < n_groups; ++gi)
-        for (const TileReq& t : groups[gi].tiles) { kv_total += t.kv_vis; kv_group[gi] += t.kv_vis; ++n_tiles; }
-    if (n_tiles == 0) return SK_OK;
+        for (const TileReq& t : groups[gi].tiles) { P.kv_total += t.kv_vis; kv_group[gi] += t.kv_vis; ++P.n_tiles; }
+    if (P.n_tiles == 0) return SK_OK;
     // One chunk length per group (= per launch), so that the workgroups of a launch cost about the
     // same whatever the session length, and every launch has enough of them to fill the chip
     // several times over (rounds of one 512-thread workgroup per CU, or of two 256-thread ones).
@@ -456,17 +624,16 @@ int run_list(sk_pool* p, ScatterBatch* sb, int n_sb, ListGroup* groups, int n_gr
         chunk_g[gi] = best;
     }
     const int64_t cap_rows = p->L.part_slots * kPartSlotRows;
-    std::vector<sk_work> work[kMaxGroups];
-    std::vector<sk_comb> comb[kMaxGroups];
-    int64_t rows_base[kMaxGroups] = {};
+    size_t bytes = 0;
     for (;;) {
         int64_t rows_used = 0;
         bool ok = true;
+        int64_t unit = 0;
         for (int gi = 0; gi < n_groups && ok; ++gi) {
             ListGroup& g = groups[gi];
             const int64_t chunk = chunk_g[gi];
-            work[gi].clear(); comb[gi].clear();
-            rows_base[gi] = rows_used;
+            P.work[gi].clear(); P.comb[gi].clear();
+            P.rows_base[gi] = rows_used;
             int64_t slot = 0;       // in units of this group's rows_per_slot, from rows_base
             // runs of consecutive tiles of one session: split-major order inside a run, so that
             // workgroups resident at the same time read the same keys (L2 reuse across row tiles)
@@ -474,12 +641,13 @@ int run_list(sk_pool* p, ScatterBatch* sb, int n_sb, ListGroup* groups, int n_gr
             while (i0 < g.tiles.size()) {
                 size_t i1 = i0;
                 int32_t max_parts = 1;
-                std::vector<int32_t> nparts, slot0;
+                std::vector<int32_t> nparts, slot0, unit0;
                 while (i1 < g.tiles.size() && g.tiles[i1].tbl_off == g.tiles[i0].tbl_off) {
                     const int32_t np = std::max<int64_t>(1, (g.tiles[i1].kv_vis + chunk - 1) / chunk);
                     nparts.push_back(np); max_parts = std::max(max_parts, np);
                     slot0.push_back(np > 1 ? (int32_t)slot : -1);
-                    if (np > 1) slot += int64_t(np) * Hkv;
+                    unit0.push_back(np > 1 ? (int32_t)unit : -1);
+                    if (np > 1) { slot += int64_t(np) * Hkv; unit += Hkv; }
                     ++i1;
                 }
                 for (int32_t part = 0; part < max_parts; ++part)
@@ -493,11 +661,14 @@ int run_list(sk_pool* p, ScatterBatch* sb, int n_sb, ListGroup* groups, int n_gr
                             w.kv_begin = int32_t(part * chunk);
                             w.kv_end = int32_t(std::min<int64_t>(t.kv_vis, (part + 1) * chunk));
                             w.part = np > 1 ? slot0[i - i0] + part * Hkv + h : -1;
+                            w.unit = np > 1 ? unit0[i - i0] + h : -1;
+                            w.part0 = np > 1 ? slot0[i - i0] + h : -1;
+                            w.n_parts = np;
                             w.hole_lo = t.hole_lo; w.hole_hi = t.hole_hi;
                             w.tok_period = t.tok_period; w.sub_blocks = t.sub_blocks;
                             if (part == np - 1)
                                 for (int e = 0; e < 2; ++e) { w.eph_blk[e] = t.eph_blk[e]; w.eph_cnt[e] = t.eph_cnt[e]; w.eph_pos0[e] = t.eph_pos0[e]; }
-                            work[gi].push_back(w);
+                            P.work[gi].push_back(w);
                         }
                     }
                 for (size_t i = i0; i < i1; ++i) {
@@ -506,7 +677,7 @@ int run_list(sk_pool* p, ScatterBatch* sb, int n_sb, ListGroup* groups, int n_gr
                         sk_comb c = {};
                         c.part0 = slot0[i - i0] + h; c.n_parts = nparts[i - i0]; c.part_stride = Hkv;
                         c.q_tok0 = g.tiles[i].q_tok0; c.n_tok = g.tiles[i].n_tok; c.kv_head = h;
-                        comb[gi].push_back(c);
+                        P.comb[gi].push_back(c);
                     }
                 }
                 i0 = i1;
@@ -514,72 +685,89 @@ int run_list(sk_pool* p, ScatterBatch* sb, int n_sb, ListGroup* groups, int n_gr
             rows_used += slot * g.v.rows_per_slot;
             if (rows_used > cap_rows) ok = false;
         }
-        size_t bytes = 0;
+        // the last workgroup of a unit merges it inside the attention kernel when the call asks for
+        // that (SK_FUSE_LIST) and every kernel in use can (the matrix-pipe instances)
+        P.fuse = p->fuse_list && unit <= p->L.sync_units;
+        for (int gi = 0; gi < n_groups; ++gi)
+            if (!P.work[gi].empty() && groups[gi].v.id == SK_KV_SIMPLE) P.fuse = false;
+        bytes = 0;
         for (int i = 0; i < n_sb; ++i) bytes += align_up(sb[i].items.size() * sizeof(sk_scatter), 256);
         for (int gi = 0; gi < n_groups; ++gi)
-            bytes += align_up(work[gi].size() * sizeof(sk_work), 256) + align_up(comb[gi].size() * sizeof(sk_comb), 256);
-        if (ok && bytes <= kMetaBytes) break;
+            bytes += align_up(P.work[gi].size() * sizeof(sk_work), 256) + align_up(P.comb[gi].size() * sizeof(sk_comb), 256);
+        if (ok && bytes <= p->L.meta_bytes) break;
         if (chunk_g[0] > (int64_t(1) << 30)) return SK_E_WORKSPACE;
         for (int gi = 0; gi < n_groups; ++gi) chunk_g[gi] *= 2;
     }
+    return ring_acquire(p, &P.slot, &P.host);
+}
+
+int launch_list(sk_pool* p, ListPlan& P, const ScatterBatch* sb, int n_sb, ListGroup* groups, int n_groups, int out_dtype, hipStream_t st)
+{
+    if (P.n_tiles == 0) return SK_OK;
+    const int Hkv = p->d.n_kv_heads;
     // one upload: scatter lists, work lists, combine lists
-    int slot; unsigned char* host;
-    int rc = ring_acquire(p, &slot, &host);
-    if (rc) return rc;
     unsigned char* ws = (unsigned char*)p->d.workspace;
-    unsigned char* dev_meta = ws + p->L.off_meta;
+    unsigned char* dev_meta = p->device ? ws + p->L.off_meta : nullptr;
     size_t off = 0, off_sb[2] = {0, 0}, off_work[kMaxGroups] = {}, off_comb[kMaxGroups] = {};
     for (int i = 0; i < n_sb; ++i) {
         off_sb[i] = off;
-        memcpy(host + off, sb[i].items.data(), sb[i].items.size() * sizeof(sk_scatter));
+        if (P.host) memcpy(P.host + off, sb[i].items.data(), sb[i].items.size() * sizeof(sk_scatter));
         off += align_up(sb[i].items.size() * sizeof(sk_scatter), 256);
     }
     for (int gi = 0; gi < n_groups; ++gi) {
         off_work[gi] = off;
-        memcpy(host + off, work[gi].data(), work[gi].size() * sizeof(sk_work));
-        off += align_up(work[gi].size() * sizeof(sk_work), 256);
+        if (P.host) memcpy(P.host + off, P.work[gi].data(), P.work[gi].size() * sizeof(sk_work));
+        off += align_up(P.work[gi].size() * sizeof(sk_work), 256);
         off_comb[gi] = off;
-        memcpy(host + off, comb[gi].data(), comb[gi].size() * sizeof(sk_comb));
-        off += align_up(comb[gi].size() * sizeof(sk_comb), 256);
+        if (P.host) memcpy(P.host + off, P.comb[gi].data(), P.comb[gi].size() * sizeof(sk_comb));
+        off += align_up(P.comb[gi].size() * sizeof(sk_comb), 256);
     }
-    rc = ring_upload(p, slot, off, st);
+    int rc = ring_upload(p, P.slot, off, st);
     if (rc) return rc;
     for (int i = 0; i < n_sb; ++i) {
         if (sb[i].items.empty()) continue;
+        if (inject(p, SK_SITE_SCATTER)) return SK_E_HIP;
+        if (!p->device) continue;
         int e = sk_launch_scatter(p->geom, sb[i].k, sb[i].v, (const sk_scatter*)(dev_meta + off_sb[i]), (int32_t)sb[i].items.size(),
                                   (int32_t*)(ws + p->L.off_tables), (unsigned char*)p->d.kv_mem, ws + p->L.off_eph, st);
         if (e) { g_last_hip = e; return SK_E_HIP; }
+        P.scatter_enqueued = true;
         p->stats.launches++;
     }
+    if (inject(p, SK_SITE_ATTENTION)) return SK_E_HIP;
+    if (!p->device) return SK_OK;
     hipEvent_t* pe = prof_begin(p, st);
     sk_launch L[kMaxGroups];
     int32_t wgs = 0, max_parts = 1;
     for (int gi = 0; gi < n_groups; ++gi) {
-        if (work[gi].empty()) continue;
+        if (P.work[gi].empty()) continue;
         ListGroup& g = groups[gi];
         fill_launch_common(p, L[gi], g.q, g.out, out_dtype, g.lse, g.v);
         L[gi].mode = SK_MODE_LIST;
-        L[gi].part_ml += rows_base[gi] * 2;
-        L[gi].part_o += rows_base[gi] * p->d.head_dim;
+        L[gi].part_ml += P.rows_base[gi] * 4;
+        L[gi].part_o += P.rows_base[gi] * p->d.head_dim;
         L[gi].work = (const sk_work*)(dev_meta + off_work[gi]);
         L[gi].comb = (const sk_comb*)(dev_meta + off_comb[gi]);
-        int e = sk_launch_attention(L[gi], g.v.id, (int32_t)work[gi].size(), st);
+        L[gi].fuse = P.fuse ? 1 : 0;
+        L[gi].wait_polls = 0;          // the workgroups of a long list are not resident together
+        int e = sk_launch_attention(L[gi], g.v.id, (int32_t)P.work[gi].size(), st);
         if (e) { g_last_hip = e; return SK_E_HIP; }
         p->stats.launches++;
-        wgs += (int32_t)work[gi].size();
-        for (const sk_comb& c : comb[gi]) max_parts = std::max(max_parts, c.n_parts);
+        wgs += (int32_t)P.work[gi].size();
+        for (const sk_comb& c : P.comb[gi]) max_parts = std::max(max_parts, c.n_parts);
     }
     if (pe) (void)hipEventRecord(pe[1], st);
-    for (int gi = 0; gi < n_groups; ++gi) {
-        if (comb[gi].empty()) continue;
-        int e = sk_launch_combine(L[gi], (int32_t)comb[gi].size(), st);
+    for (int gi = 0; gi < n_groups && !P.fuse; ++gi) {
+        if (P.comb[gi].empty()) continue;
+        int e = sk_launch_combine(L[gi], (int32_t)P.comb[gi].size(), st);
         if (e) { g_last_hip = e; return SK_E_HIP; }
         p->stats.launches++;
     }
     if (pe) (void)hipEventRecord(pe[2], st);
-    p->stats.kv_bytes_streamed += kv_total * 2 * Hkv * p->d.head_dim * p->L.elem;
-    p->last.workgroups = wgs; p->last.n_splits = max_parts; p->last.row_tiles = (int32_t)n_tiles;
+    p->stats.kv_bytes_streamed += P.kv_total * 2 * Hkv * p->d.head_dim * p->L.elem;
+    p->last.workgroups = wgs; p->last.n_splits = max_parts; p->last.row_tiles = (int32_t)P.n_tiles;
     p->last.kernel_variant = groups[0].v.id;
+    p->last.fused_merge = P.fuse ? 1 : 0;
     for (int gi = n_groups - 1; gi >= 0; --gi) if (!groups[gi].tiles.empty()) p->last.kernel_variant = groups[gi].v.id;
     return SK_OK;
 }
@@ -644,8 +832,14 @@ int sk_pool_create(const sk_pool_desc* desc, sk_pool** out)
     p->no_256 = env_on("SK_NO_256");
     p->no_pack = env_on("SK_NO_PACK");
     p->no_interleave = env_on("SK_NO_INTERLEAVE");
+    p->fuse = !env_on("SK_NO_FUSE");
+    p->fuse_list = env_on("SK_FUSE_LIST");
+    if (const char* t = getenv("SK_WAIT_POLLS")) { int x = atoi(t); if (x >= 0) p->wait_polls = x; }
     if (!meta_only) {
-        hipError_t e = hipHostMalloc((void**)&p->ring, kMetaBytes * kRingSlots, hipHostMallocDefault);
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+            p->n_cus = cus;
+        hipError_t e = hipHostMalloc((void**)&p->ring, p->L.meta_bytes * kRingSlots, hipHostMallocDefault);
         if (e != hipSuccess) { g_last_hip = (int)e; delete p; return SK_E_HIP; }
         for (int i = 0; i < kRingSlots; ++i) {
             e = hipEventCreateWithFlags(&p->ring_ev[i], hipEventDisableTiming);
@@ -655,6 +849,10 @@ int sk_pool_create(const sk_pool_desc* desc, sk_pool** out)
         std::vector<int32_t> ident((size_t)L.eph_blocks);
         for (size_t i = 0; i < ident.size(); ++i) ident[i] = (int32_t)i;
         e = hipMemcpy((unsigned char*)desc->workspace + L.off_ident, ident.data(), ident.size() * 4, hipMemcpyHostToDevice);
+        if (e != hipSuccess) { g_last_hip = (int)e; sk_pool_destroy(p); return SK_E_HIP; }
+        // the merge counters start at zero; every launch leaves them at zero
+        e = hipMemset((unsigned char*)desc->workspace + L.off_sync, 0, size_t(L.sync_units) * 8);
+        if (e == hipSuccess) e = hipDeviceSynchronize();
         if (e != hipSuccess) { g_last_hip = (int)e; sk_pool_destroy(p); return SK_E_HIP; }
     }
     *out = p;
@@ -748,28 +946,36 @@ int sk_session_append(sk_pool* p, int32_t id, const void* q, const void* k, cons
         if (!k || !v || (!q) != (!out)) return SK_E_INVAL;
         if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse)) return SK_E_INVAL;
         if (q) { int rc = check_out_dtype(p, out_dtype); if (rc) return rc; }
-        Variant vv;
-        if (q && !pick_variant(p, L, vv)) return SK_E_SHAPE;
     }
     if (s->len + L > p->L.max_session_tokens) return SK_E_NOMEM;
     const int64_t need = blocks_needed(p, s->len, L);
-    const bool unshare = tail_shared(p, s);
-    if (need + (unshare ? 1 : 0) > (int64_t)p->free_blocks.size()) return SK_E_NOMEM;
-    // from here on nothing can fail for lack of resources
+    if (need + (tail_shared(p, s) ? 1 : 0) > (int64_t)p->free_blocks.size()) return SK_E_NOMEM;
+    // everything else that can refuse the call, before it changes anything: the decomposition of the
+    // attention, and the ring slot of a scatter list too long for the kernel arguments
     hipStream_t st = (hipStream_t)hip_stream;
-    if (unshare) { int rc = unshare_tail(p, s, st); if (rc) return rc; }
-    const int64_t first_new = (int64_t)s->blocks.size() - (unshare ? 1 : 0);
     const int64_t n = s->len;
-    take_blocks(p, s, need);
-    s->len = n + L;
-    p->stats.tokens_appended += L;
-    if (!p->device) return SK_OK;
+    const bool attend = p->device ? q != nullptr : true;
+    RegPlan plan;
+    if (attend) {
+        int rc = plan_regular(p, id, L, (int32_t)n, n + L, 0, 0, s->frozen, s->win, 0, plan);
+        if (rc) return rc;
+    }
+    ScatterSlot ss;
+    { int rc = scatter_reserve(p, scatter_groups(n, L), ss); if (rc) return rc; }
+    // from here on only a failing HIP call can stop the call; what it changed is taken back
+    Undo u;
+    int64_t first_new = 0;
+    { int rc = grow_session(p, s, L, u, &first_new, st); if (rc) return rc; }
     std::vector<sk_scatter> items;
     build_scatter(p, s, id, n, 0, L, first_new, false, 0, items);
-    int rc = upload_and_scatter(p, items, k, v, st);
-    if (rc) return rc;
-    if (!q) return SK_OK;
-    return run_regular(p, id, q, L, (int32_t)n, n + L, 0, 0, out, out_dtype, lse, 0, st);
+    int rc = scatter_launch(p, ss, items, k, v, st);
+    if (rc) { rollback(p, u, false); return rc; }
+    if (attend) {
+        rc = launch_regular(p, plan, q, out, out_dtype, lse, st);
+        if (rc) { rollback(p, u, true); return rc; }
+    }
+    p->stats.tokens_appended += L;
+    return SK_OK;
 }
 
 int sk_session_query(sk_pool* p, int32_t id, const void* q, const void* k, const void* v, int32_t nq,
@@ -790,15 +996,23 @@ int sk_session_query(sk_pool* p, int32_t id, const void* q, const void* k, const
     Variant vv;
     if (!pick_variant(p, nq, vv)) return SK_E_SHAPE;
     hipStream_t st = (hipStream_t)hip_stream;
-    p->stats.tokens_queried += nq;
+    RegPlan plan;
+    if (k) rc = plan_regular(p, id, nq, (int32_t)s->len, s->len, nq, (int32_t)s->len, s->frozen, s->win, n_splits, plan);
+    else rc = plan_regular(p, id, nq, SK_NO_CAUSAL, s->len, 0, 0, s->frozen, s->win, n_splits, plan);
+    if (rc) return rc;
     if (k) {
+        ScatterSlot ss;
+        rc = scatter_reserve(p, scatter_groups(0, nq), ss);
+        if (rc) return rc;
         std::vector<sk_scatter> items;
         build_scatter(p, nullptr, id, 0, 0, nq, 0, true, 0, items);
-        rc = upload_and_scatter(p, items, k, v, st);
+        rc = scatter_launch(p, ss, items, k, v, st);
         if (rc) return rc;
-        return run_regular(p, id, q, nq, (int32_t)s->len, s->len, nq, (int32_t)s->len, out, out_dtype, lse, n_splits, st);
     }
-    return run_regular(p, id, q, nq, SK_NO_CAUSAL, s->len, 0, 0, out, out_dtype, lse, n_splits, st);
+    rc = launch_regular(p, plan, q, out, out_dtype, lse, st);
+    if (rc) return rc;
+    p->stats.tokens_queried += nq;
+    return SK_OK;
 }
 
 int sk_batch_step(sk_pool* p, int32_t n_items, const int32_t* session_id, const int32_t* op, const int32_t* cu_tokens,
@@ -831,6 +1045,12 @@ int sk_batch_step(sk_pool* p, int32_t n_items, const int32_t* session_id, const 
     const int64_t total = cu_tokens[n_items];
     if (total > p->L.max_batch_tokens) return SK_E_WORKSPACE;
     if (need_blocks > (int64_t)p->free_blocks.size()) return SK_E_NOMEM;
+    {   // staging blocks of the queries that bring their own K/V
+        int64_t eph_need = 0;
+        for (int i = 0; i < n_items; ++i)
+            if (op[i] == SK_OP_QUERY_B) eph_need += (int64_t(cu_tokens[i + 1]) - cu_tokens[i] + 15) / 16;
+        if (eph_need > p->L.eph_blocks) return SK_E_WORKSPACE;
+    }
     if (p->device) {
         if (!q || !out || (any_kv && (!k || !v))) return SK_E_INVAL;
         if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse)) return SK_E_INVAL;
@@ -839,12 +1059,19 @@ int sk_batch_step(sk_pool* p, int32_t n_items, const int32_t* session_id, const 
         Variant vv;
         if (!pick_variant(p, 1, vv)) return SK_E_SHAPE;
     }
-    // nothing below fails for lack of pool resources
+    // From here on the sessions change; whatever stops the call afterwards (the lists do not fit the
+    // workspace, a HIP call fails) takes every change back, in reverse order.
     ScatterBatch sb;
     sb.k = k; sb.v = v;
     ListGroup groups[3];
     const bool allow_256 = !p->no_256;
     int64_t eph_cursor = 0;
+    std::vector<Undo> undo;
+    int64_t appended = 0, queried = 0;
+    auto take_back = [&](bool keep_copies) {
+        for (size_t i = undo.size(); i-- > 0;) rollback(p, undo[i], keep_copies);
+    };
+    hipStream_t st = (hipStream_t)hip_stream;
     for (int i = 0; i < n_items; ++i) {
         Session* s = get_session(p, session_id[i]);
         const int32_t T = cu_tokens[i + 1] - cu_tokens[i];
@@ -856,18 +1083,16 @@ int sk_batch_step(sk_pool* p, int32_t n_items, const int32_t* session_id, const 
         base.tbl_off = tbl_off;
         base.hole_lo = (int32_t)s->frozen; base.hole_hi = (int32_t)s->win;
         if (op[i] == SK_OP_APPEND) {
-            const bool unshare = tail_shared(p, s);
-            if (unshare) { int rc = unshare_tail(p, s, (hipStream_t)hip_stream); if (rc) return rc; }
-            const int64_t first_new = (int64_t)s->blocks.size() - (unshare ? 1 : 0);
-            take_blocks(p, s, blocks_needed(p, n, T));
-            s->len = n + T;
-            p->stats.tokens_appended += T;
-            if (!p->device) continue;
+            Undo u;
+            int64_t first_new = 0;
+            int rc = grow_session(p, s, T, u, &first_new, st);
+            if (rc) { take_back(false); return rc; }
+            undo.push_back(u);
+            appended += T;
             build_scatter(p, s, id, n, cu_tokens[i], T, first_new, false, 0, sb.items);
             base.pos0 = (int32_t)n; base.kv_vis = int32_t(n + T);
         } else {
-            if (!p->device) continue;
-            p->stats.tokens_queried += T;
+            queried += T;
             if (op[i] == SK_OP_QUERY_B) {
                 build_scatter(p, nullptr, id, 0, cu_tokens[i], T, 0, true, eph_cursor, sb.items);
                 base.pos0 = (int32_t)n; base.kv_vis = (int32_t)n;
@@ -880,13 +1105,19 @@ int sk_batch_step(sk_pool* p, int32_t n_items, const int32_t* session_id, const 
         // items of more than 128 rows per KV head (the appends) go to the 256-row kernel, which is
         // launched first; then the 128-row items, then the small ones
         Variant vv;
-        pick_variant(p, T, vv, allow_256);
+        if (!pick_variant(p, T, vv, allow_256)) { take_back(false); return SK_E_SHAPE; }
         ListGroup& g = groups[vv.id == SK_KV_MFMA64 ? 2 : vv.id == SK_KV_MFMA128 ? 1 : 0];
         g.v = vv; g.q = q; g.out = out; g.lse = lse;
         add_tiles(g, base, cu_tokens[i], T);
     }
-    if (!p->device) return SK_OK;
-    return run_list(p, &sb, 1, groups, 3, out_dtype, (hipStream_t)hip_stream);
+    ListPlan plan;
+    int rc = plan_list(p, &sb, 1, groups, 3, plan);
+    if (rc) { take_back(false); return rc; }
+    rc = launch_list(p, plan, &sb, 1, groups, 3, out_dtype, st);
+    if (rc) { take_back(plan.scatter_enqueued); return rc; }
+    p->stats.tokens_appended += appended;
+    p->stats.tokens_queried += queried;
+    return SK_OK;
 }
 
 int sk_session_query_shared_prefix(sk_pool* p, int32_t id, const void* qp, const void* kp, const void* vp, int32_t P,
@@ -914,7 +1145,6 @@ int sk_session_query_shared_prefix(sk_pool* p, int32_t id, const void* qp, const
     if (!pick_variant(p, 1, vtest)) return SK_E_SHAPE;
     const int64_t n = s->len;
     const int32_t tbl_off = int32_t(int64_t(id) * p->L.max_blocks_per_session);
-    p->stats.tokens_queried += total;
     ScatterBatch sb[2];
     ListGroup groups[2];
     if (P > 0) {
@@ -956,7 +1186,13 @@ int sk_session_query_shared_prefix(sk_pool* p, int32_t id, const void* qp, const
             } else add_tiles(groups[1], base, j * Sfx, Sfx);
         }
     }
-    return run_list(p, sb, 2, groups, 2, out_dtype, (hipStream_t)hip_stream);
+    ListPlan plan;
+    rc = plan_list(p, sb, 2, groups, 2, plan);
+    if (rc) return rc;
+    rc = launch_list(p, plan, sb, 2, groups, 2, out_dtype, (hipStream_t)hip_stream);
+    if (rc) return rc;
+    p->stats.tokens_queried += total;
+    return SK_OK;
 }
 
 int sk_session_gather(const sk_pool* p, int32_t id, int64_t first, int64_t count, void* k_out, void* v_out, void* hip_stream)
@@ -1020,28 +1256,35 @@ int sk_session_evict_oldest(sk_pool* p, int32_t id, int64_t n_tokens, void* hip_
     if (!s) return SK_E_BADSESSION;
     if (n_tokens < 0 || n_tokens > s->len - s->win) return SK_E_INVAL;
     if (n_tokens == 0) return SK_OK;
-    s->win += n_tokens;
-    p->stats.tokens_evicted += n_tokens;
     // blocks that lie entirely inside the hole go back to the pool; storage indices behind them move down
     const int64_t B = p->d.block_tokens;
-    const int64_t b0 = (s->frozen + B - 1) / B, b1 = s->win / B;
-    if (b1 <= b0) return SK_OK;
+    const int64_t win = s->win + n_tokens;
+    const int64_t b0 = (s->frozen + B - 1) / B, b1 = win / B;
+    if (b1 <= b0) {                  // no whole block is freed: the window start moves, nothing else
+        s->win = win;
+        p->stats.tokens_evicted += n_tokens;
+        return SK_OK;
+    }
+    // The moved tail of the session's device block table is rewritten (ordered on the caller's
+    // stream); the host side changes only once that copy is enqueued, so a failure leaves the
+    // session as it was.
+    const size_t n_moved = s->blocks.size() - (size_t)b1;
+    if (n_moved > 0) {
+        int slot; unsigned char* host;
+        int rc = ring_acquire(p, &slot, &host);
+        if (rc) return rc;
+        const size_t bytes = n_moved * sizeof(int32_t);
+        if (host) memcpy(host, s->blocks.data() + b1, bytes);
+        int32_t* dev_tbl = p->device ? (int32_t*)((unsigned char*)p->d.workspace + p->L.off_tables) + int64_t(id) * p->L.max_blocks_per_session + b0
+                                     : nullptr;
+        rc = ring_copy(p, slot, dev_tbl, bytes, (hipStream_t)hip_stream);
+        if (rc) return rc;
+    }
     const int64_t k = b1 - b0;
     for (int64_t b = b0; b < b1; ++b) release_block(p, s->blocks[(size_t)b]);
     s->blocks.erase(s->blocks.begin() + b0, s->blocks.begin() + b1);
-    s->win -= k * B; s->len -= k * B;
-    if (!p->device || s->blocks.size() == (size_t)b0) return SK_OK;
-    // rewrite the moved tail of the session's device block table (ordered on the caller's stream)
-    int slot; unsigned char* host;
-    int rc = ring_acquire(p, &slot, &host);
-    if (rc) return rc;
-    const size_t bytes = (s->blocks.size() - (size_t)b0) * sizeof(int32_t);
-    memcpy(host, s->blocks.data() + b0, bytes);
-    int32_t* dev_tbl = (int32_t*)((unsigned char*)p->d.workspace + p->L.off_tables) + int64_t(id) * p->L.max_blocks_per_session + b0;
-    hipStream_t st = (hipStream_t)hip_stream;
-    SK_HIP(hipMemcpyAsync(dev_tbl, host, bytes, hipMemcpyHostToDevice, st));
-    SK_HIP(hipEventRecord(p->ring_ev[slot], st));
-    p->ring_used[slot] = true;
+    s->win = win - k * B; s->len -= k * B;
+    p->stats.tokens_evicted += n_tokens;
     return SK_OK;
 }
 
@@ -1061,39 +1304,51 @@ int sk_session_fork(sk_pool* p, int32_t src_id, int64_t n_prefix, int32_t* out_i
     const bool tail_partial = len % B != 0;      // the new session will write into its last block: it gets a copy
     if (tail_partial && p->free_blocks.empty()) return SK_E_NOMEM;
     const int32_t id = p->free_ids.back();
+    std::vector<int32_t> blocks(src->blocks.begin(), src->blocks.begin() + n_blk);
+    int32_t tail_src = -1;
+    if (tail_partial) { tail_src = blocks.back(); blocks.back() = p->free_blocks.front(); }
+    // Device work first (the new session's block table, then the copy of the partly filled last block,
+    // all KV heads), into places no live session reads; the host side changes only when both are
+    // enqueued, so a failure leaves the pool as it was.
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (n_blk > 0) {
+        int slot; unsigned char* host;
+        int rc = ring_acquire(p, &slot, &host);
+        if (rc) return rc;
+        const size_t bytes = (size_t)n_blk * sizeof(int32_t);
+        if (host) memcpy(host, blocks.data(), bytes);
+        int32_t* dev_tbl = p->device ? (int32_t*)((unsigned char*)p->d.workspace + p->L.off_tables) + int64_t(id) * p->L.max_blocks_per_session
+                                     : nullptr;
+        rc = ring_copy(p, slot, dev_tbl, bytes, st);
+        if (rc) return rc;
+        if (tail_partial) {
+            if (inject(p, SK_SITE_BLOCK_COPY)) return SK_E_HIP;
+            if (p->device) {
+                int e = sk_launch_copy_block(p->geom, (unsigned char*)p->d.kv_mem, tail_src, blocks.back(), st);
+                if (e) { g_last_hip = e; return SK_E_HIP; }
+            }
+        }
+    }
     p->free_ids.pop_back();
     Session& d = p->sessions[id];
     d.live = true; d.frozen = frozen; d.win = win; d.len = len;
-    d.blocks.assign(src->blocks.begin(), src->blocks.begin() + n_blk);
+    d.blocks.swap(blocks);
     for (int64_t i = 0; i < n_blk - (tail_partial ? 1 : 0); ++i) p->refcnt[(size_t)d.blocks[(size_t)i]]++;
-    int32_t tail_src = -1;
     if (tail_partial) {
-        tail_src = d.blocks.back();
-        d.blocks.back() = p->free_blocks.front();
         p->refcnt[(size_t)d.blocks.back()] = 1;
         p->free_blocks.pop_front();
         p->blocks_in_use++;
     }
     *out_id = id;
     p->stats.forks++;
-    if (!p->device || n_blk == 0) return SK_OK;
-    hipStream_t st = (hipStream_t)hip_stream;
-    // the new session's block table, then the copy of the partly filled last block (all KV heads)
-    int slot; unsigned char* host;
-    int rc = ring_acquire(p, &slot, &host);
-    if (rc) return rc;
-    const size_t bytes = (size_t)n_blk * sizeof(int32_t);
-    memcpy(host, d.blocks.data(), bytes);
-    int32_t* dev_tbl = (int32_t*)((unsigned char*)p->d.workspace + p->L.off_tables) + int64_t(id) * p->L.max_blocks_per_session;
-    SK_HIP(hipMemcpyAsync(dev_tbl, host, bytes, hipMemcpyHostToDevice, st));
-    SK_HIP(hipEventRecord(p->ring_ev[slot], st));
-    p->ring_used[slot] = true;
-    if (tail_partial) {
-        unsigned char* kv = (unsigned char*)p->d.kv_mem;
-        SK_HIP(hipMemcpy2DAsync(kv + int64_t(d.blocks.back()) * p->L.blk_stride, (size_t)p->L.head_stride,
-                                kv + int64_t(tail_src) * p->L.blk_stride, (size_t)p->L.head_stride,
-                                (size_t)p->L.blk_stride, (size_t)p->d.n_kv_heads, hipMemcpyDeviceToDevice, st));
-    }
+    return SK_OK;
+}
+
+int sk_pool_inject_failure(sk_pool* p, int32_t site, int32_t countdown)
+{
+    if (!p || site < 0 || site > SK_SITE_PLAN || countdown < 0) return SK_E_INVAL;
+    p->inject_site = countdown > 0 ? site : 0;
+    p->inject_countdown = countdown;
     return SK_OK;
 }
 
@@ -1166,6 +1421,6 @@ const char* sk_strerror(int status)
 }
 
 int sk_last_hip_error(void) { return g_last_hip; }
-int sk_version(void) { return 1; }
+int sk_version(void) { return 2; }
 
 }  // extern "C"

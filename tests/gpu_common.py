@@ -8,12 +8,12 @@ Because i.i.d. N(0,1) inputs at long context give outputs of magnitude ~sqrt(e/n
 those absolute bounds), two tighter checks ride along so that a dropped or duplicated key range
 cannot pass: per output row, max |diff| <= 2^-5 (bf16) or 1e-4 (fp32) times the row's rms (the
 bf16 rounding of the softmax weights bounds the error of a row by 2^-8 max|v|, about 2^-6 of the
-rms of a row that sees two keys, far less of longer rows), and |lse diff| <= 4e-3 (bf16) or 2e-5
-(fp32; lse ~ ln n + 1/2 is O(10), so this is ~2 ulp of fp32 at that magnitude).  The bf16 bound on
-the lse is ln(1 + 2^-8) = 3.9e-3: the kernel sums the weights as the matrix pipe sees them, rounded
-to bf16 (relative error at most 2^-8 each), so that an output row is an exact convex combination of
-values; the sum, and with it the lse, carries at most that relative error, and far less over long
-rows, where the roundings average out.
+rms of a row that sees two keys, far less of longer rows), and |lse diff| <= 1e-3 (bf16) or 2e-5
+(fp32; lse ~ ln n + 1/2 is O(10), so this is ~2 ulp of fp32 at that magnitude).  The kernel
+normalises an output row by the sum of its weights as the matrix pipe sees them (rounded to bf16), so
+that the row is an exact convex combination of values, and takes the lse from the sum of the
+unrounded weights, kept beside it in fp32: what is left in the lse is the hardware exp2/log2 (about
+1 ulp each) and the fp32 summation, a few 1e-6 relative to a sum, far inside 1e-3.
 """
 import numpy as np
 import torch
@@ -23,7 +23,7 @@ import paper_2605_13784_amd as sk
 from workloads import synth
 
 TOL = {
-    "bf16": dict(max_abs=1e-2, mean_abs=1e-3, rel=2.0 ** -5, lse=4e-3),
+    "bf16": dict(max_abs=1e-2, mean_abs=1e-3, rel=2.0 ** -5, lse=1e-3),
     "f32": dict(max_abs=1e-5, mean_abs=1e-5, rel=1e-4, lse=2e-5),
 }
 

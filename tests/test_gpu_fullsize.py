@@ -13,10 +13,29 @@ from gpu_common import TOL, compare, dev
 pytestmark = pytest.mark.gpu
 
 
-def _sample_rows(rng, n_tok, n_heads, count, always=()):
+def _tile_rows(T, shape):
+    """Height of the row tile the library gives a call of T tokens (rows per KV head = T x group):
+    256 rows above 128, else 128 above 64, else 64."""
+    rows = T * shape.group
+    return 256 if rows > 128 else 128 if rows > 64 else 64
+
+
+def _sample_rows(rng, n_tok, shape, extra=0, always=(), tile_rows=None):
+    """Rows (token, query head) to check against the oracle, stratified over the launch: for every
+    (row tile, KV head) - one workgroup column of the kernel - the tile's first row, its last row and
+    one row drawn at random inside it, so that a fault confined to one tile of one head cannot go
+    unsampled; plus `extra` rows drawn uniformly."""
+    G, Hkv = shape.group, shape.n_kv_heads
+    tpt = max(1, (tile_rows or _tile_rows(n_tok, shape)) // G)
     rows = set(always)
-    while len(rows) < min(count, n_tok * n_heads):
-        rows.add((int(rng.integers(n_tok)), int(rng.integers(n_heads))))
+    for t0 in range(0, n_tok, tpt):
+        t1 = min(t0 + tpt, n_tok) - 1
+        for g in range(Hkv):
+            rows.add((t0, g * G))
+            rows.add((t1, g * G + G - 1))
+            rows.add((int(rng.integers(t0, t1 + 1)), g * G + int(rng.integers(G))))
+    for _ in range(extra):
+        rows.add((int(rng.integers(n_tok)), int(rng.integers(shape.n_q_heads))))
     return sorted(rows)
 
 
@@ -58,7 +77,7 @@ def test_single_session_full_context(n, L, nq, n_rows, B):
     _build(pool, sid, ref, n - L, shape, gen)
     q, k, v = synth.draw_qkv(gen, L, shape)
     out, lse = pool.sk_session_append(sid, dev(q), dev(k), dev(v))
-    rows = _sample_rows(rng, L, shape.n_q_heads, n_rows, always=[(0, 0), (L - 1, shape.n_q_heads - 1)])
+    rows = _sample_rows(rng, L, shape, extra=n_rows)
     ro, rl = ref.append(synth.to_raw(q), synth.to_raw(k), synth.to_raw(v), rows=rows)
     _check_rows("append at %d" % (n - L), out, lse, rows, ro, rl, shape.dtype)
     assert pool.sk_session_length(sid) == n
@@ -69,7 +88,7 @@ def test_single_session_full_context(n, L, nq, n_rows, B):
         np.testing.assert_array_equal(synth.to_raw(kc.cpu()), ref.K[first:first + 1024])
         np.testing.assert_array_equal(synth.to_raw(vc.cpu()), ref.V[first:first + 1024])
     qq, kq, vq = synth.draw_qkv(gen, nq, shape)
-    rows = _sample_rows(rng, nq, shape.n_q_heads, n_rows, always=[(0, 0), (nq - 1, shape.n_q_heads - 1)])
+    rows = _sample_rows(rng, nq, shape, extra=n_rows)
     out, lse = pool.sk_session_query(sid, dev(qq))
     geo = pool.sk_pool_last_launch()
     assert geo["workgroups"] >= 256                      # the configuration bench.py times fills the chip
@@ -98,7 +117,7 @@ def test_registered_question_batch_at_65536():
     _build(pool, sid, ref, n - L, shape, gen, piece=1024)
     q, k, v = synth.draw_qkv(gen, L, shape)
     out, lse = pool.sk_session_append(sid, dev(q), dev(k), dev(v))
-    rows = _sample_rows(rng, L, shape.n_q_heads, 24)
+    rows = _sample_rows(rng, L, shape, extra=8)
     ro, rl = ref.append(synth.to_raw(q), synth.to_raw(k), synth.to_raw(v), rows=rows)
     _check_rows("append", out, lse, rows, ro, rl, shape.dtype)
     qp, kp, vp = synth.draw_qkv(gen, P, shape)
@@ -106,15 +125,16 @@ def test_registered_question_batch_at_65536():
     r4 = lambda t, H: t.reshape(NQ, Sfx, H, shape.head_dim)
     op, lp, os_, ls = pool.sk_session_query_shared_prefix(sid, dev(qp), dev(kp), dev(vp), dev(r4(qs, 64)),
                                                           dev(r4(ks, 8)), dev(r4(vs, 8)))
-    rows = _sample_rows(rng, P, shape.n_q_heads, 12, always=[(0, 0), (P - 1, 63)])
+    rows = _sample_rows(rng, P, shape, extra=4)
     ro, rl = ref.query(synth.to_raw(qp), synth.to_raw(kp), synth.to_raw(vp), rows=rows)
     _check_rows("prefix rows", op, lp, rows, ro, rl, shape.dtype)
-    for j in (0, 31, 63):
+    # every question (four of them share a 256-row tile): first and last row of every KV head, one at random
+    for j in range(NQ):
         sl = slice(j * Sfx, (j + 1) * Sfx)
         qj = np.concatenate([synth.to_raw(qp), synth.to_raw(qs[sl])])
         kj = np.concatenate([synth.to_raw(kp), synth.to_raw(ks[sl])])
         vj = np.concatenate([synth.to_raw(vp), synth.to_raw(vs[sl])])
-        rows = _sample_rows(rng, Sfx, shape.n_q_heads, 8, always=[(Sfx - 1, 63)])
+        rows = _sample_rows(rng, Sfx, shape, tile_rows=Sfx * shape.group)
         ro, rl = ref.query(qj, kj, vj, rows=[(P + i, h) for i, h in rows])
         _check_rows("question %d" % j, os_[j], ls[j], rows, ro, rl, shape.dtype)
     assert pool.sk_session_length(sid) == n
@@ -122,8 +142,9 @@ def test_registered_question_batch_at_65536():
 
 def test_multi_tenant_step_at_full_size():
     """Workload 4: 48 sessions, lengths log-uniform over 2K-64K, 16-token blocks in a seeded random
-    order; one step appends 128-1024 tokens on 16 sessions and queries 8-64 tokens on 32; two sampled
-    rows per item against the oracle, commits checked bit for bit on the appended ranges."""
+    order; one step appends 128-1024 tokens on 16 sessions and queries 8-64 tokens on 32; three rows of
+    every (row tile, KV head) of every item against the oracle, commits checked bit for bit on the
+    appended ranges."""
     shape = synth.CFG4
     gen = synth.generator(4, stream=20)
     rng = np.random.default_rng(4)
@@ -160,7 +181,7 @@ def test_multi_tenant_step_at_full_size():
     qr, kr, vr = synth.to_raw(q), synth.to_raw(k), synth.to_raw(v)
     for j, i in enumerate(order):
         a, b = int(cu[j]), int(cu[j + 1])
-        rows = _sample_rows(rng, b - a, shape.n_q_heads, 2, always=[(b - a - 1, 31)])
+        rows = _sample_rows(rng, b - a, shape)
         if ops[j] == sk.SK_OP_APPEND:
             ro, rl = refs[i].append(qr[a:b], kr[a:b], vr[a:b], rows=rows)
             kc, vc = pool.sk_session_gather(sids[i], lengths[i], b - a)

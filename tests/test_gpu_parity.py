@@ -135,3 +135,56 @@ def test_large_logits_and_needle():
         torch.cuda.synchronize()
         got = out[1, 9].cpu()
         assert torch.allclose(got, v[pos, 2].float(), atol=1e-2), "needle at %d not retrieved" % pos
+
+
+@pytest.mark.parametrize("scale", [0.05, 0.2])
+def test_custom_softmax_scale(scale):
+    """Eq. 1's 1/sqrt(d_k) is the default, not the only scale: a pool created with softmax_scale set
+    (0.05 flattens the weights, 0.2 sharpens them well beyond 1/sqrt(128) = 0.088) against an oracle
+    given the same number, through every entry point: appends (several row tiles, split merge),
+    cache-only and own-K/V queries with several split counts, a ragged multi-session step and a
+    shared-prefix question batch; fp32 pool once as well."""
+    import oracle
+    import paper_2605_13784_amd as sk
+    shape = synth.CFG2
+    gen = synth.generator(2, stream=300 + int(scale * 100))
+    pr = Pair(shape, block_tokens=16, n_blocks=400, max_sessions=3, max_batch_tokens=1024, softmax_scale=scale)
+    a, b = pr.create(), pr.create()
+    for sid, Ls in ((a, [300, 700, 41]), (b, [90, 1])):
+        for L in Ls:
+            q, k, v = synth.draw_qkv(gen, L, shape)
+            pr.append(sid, q, k, v, name="scale %.2f append %d" % (scale, L))
+    for nq in (32, 5):
+        q, k, v = synth.draw_qkv(gen, nq, shape)
+        for S in (0, 1, 5):
+            pr.query(a, q, n_splits=S, name="scale %.2f query A nq=%d S=%d" % (scale, nq, S))
+            pr.query(a, q, k, v, n_splits=S, name="scale %.2f query B nq=%d S=%d" % (scale, nq, S))
+    # ragged step: append on b, own-K/V query on a
+    counts = [130, 20]
+    cu = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    q, k, v = synth.draw_qkv(gen, int(cu[-1]), shape)
+    out, lse = pr.pool.sk_batch_step([b, a], [sk.SK_OP_APPEND, sk.SK_OP_QUERY_B], cu, dev(q), dev(k), dev(v))
+    qr, kr, vr = synth.to_raw(q), synth.to_raw(k), synth.to_raw(v)
+    ro, rl = pr.oracles[b].append(qr[:130], kr[:130], vr[:130])
+    compare("scale %.2f step append" % scale, out[:130], lse[:130], ro, rl, shape.dtype)
+    ro, rl = pr.oracles[a].query(qr[130:], kr[130:], vr[130:])
+    compare("scale %.2f step query" % scale, out[130:], lse[130:], ro, rl, shape.dtype)
+    pr.check_cache(b)
+    # question batch on a
+    P, NQ, Sfx = 16, 6, 8
+    qp, kp, vp = synth.draw_qkv(gen, P, shape)
+    qs, ks, vs = synth.draw_qkv(gen, NQ * Sfx, shape)
+    r4 = lambda t: t.reshape(NQ, Sfx, t.shape[1], shape.head_dim)
+    op, lp, os_, ls = pr.pool.sk_session_query_shared_prefix(a, dev(qp), dev(kp), dev(vp), dev(r4(qs)), dev(r4(ks)), dev(r4(vs)))
+    rop, rlp, ros, rls = pr.oracles[a].query_shared_prefix(synth.to_raw(qp), synth.to_raw(kp), synth.to_raw(vp),
+                                                           synth.to_raw(r4(qs)), synth.to_raw(r4(ks)), synth.to_raw(r4(vs)))
+    compare("scale %.2f prefix" % scale, op, lp, rop, rlp, shape.dtype)
+    compare("scale %.2f suffixes" % scale, os_, ls, ros, rls, shape.dtype)
+    # the fp32 path takes the scale the same way
+    pf = Pair(synth.CFG1, block_tokens=16, n_blocks=40, softmax_scale=scale)
+    s = pf.create()
+    q, k, v = synth.draw_qkv(gen, 100, synth.CFG1)
+    pf.append(s, q, k, v, name="fp32 scale %.2f append" % scale)
+    q, k, v = synth.draw_qkv(gen, 9, synth.CFG1)
+    pf.query(s, q, n_splits=3, name="fp32 scale %.2f query A" % scale)
+    pf.query(s, q, k, v, name="fp32 scale %.2f query B" % scale)

@@ -196,3 +196,63 @@ def test_two_pools_on_two_streams():
         p1.check_cache(a); p1.check_cache(f)
     with torch.cuda.stream(s2):
         p2.check_cache(b); p2.check_cache(c)
+
+
+def _pool_with_env(env, shape, **kw):
+    """The tuning switches are read when a pool is created."""
+    import os
+    old = {k: os.environ.get(k) for k in env}
+    os.environ.update(env)
+    try:
+        return sk.Pool(shape.dtype, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, **kw)
+    finally:
+        for k, v in old.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v
+
+
+def test_merge_inside_the_kernel_equals_the_separate_combine_bit_for_bit():
+    """The split partials of a call are merged by whichever workgroups happen to do it: all of a row
+    tile's workgroups sharing the rows (they waited for each other), the last one alone (nobody
+    waits: SK_WAIT_POLLS=0), or a second kernel (SK_NO_FUSE=1).  One function merges a row in split
+    order in all three, so outputs and log-sum-exps must agree to the last bit, call after call (the
+    counters the workgroups meet at are left at zero by every launch); also for a batched step and a
+    question batch with SK_FUSE_LIST=1."""
+    shape = synth.CFG2
+    gen = synth.generator(2, stream=77)
+    kw = dict(block_tokens=16, n_blocks=700, max_sessions=3, max_batch_tokens=2048)
+    pools = [_pool_with_env({}, shape, **kw), _pool_with_env({"SK_WAIT_POLLS": "0"}, shape, **kw),
+             _pool_with_env({"SK_NO_FUSE": "1"}, shape, **kw), _pool_with_env({"SK_FUSE_LIST": "1"}, shape, **kw)]
+    sids = [(p.sk_session_create(), p.sk_session_create()) for p in pools]
+
+    def same(results, what):
+        for r in results[1:]:
+            for x, y in zip(results[0], r):
+                assert torch.equal(x, y), what
+
+    for L in (600, 256, 1, 2000, 77, 1300):
+        q, k, v = [dev(t) for t in synth.draw_qkv(gen, L, shape)]
+        same([p.sk_session_append(s[0], q, k, v) for p, s in zip(pools, sids)], "append %d" % L)
+    assert pools[0].sk_pool_last_launch()["fused_merge"] == 1 and pools[2].sk_pool_last_launch()["fused_merge"] == 0
+    for nq in (32, 16, 100, 3):
+        q, k, v = [dev(t) for t in synth.draw_qkv(gen, nq, shape)]
+        for S in (0, 3, 40):
+            same([p.sk_session_query(s[0], q, n_splits=S) for p, s in zip(pools, sids)], "query A %d S=%d" % (nq, S))
+            same([p.sk_session_query(s[0], q, k, v, n_splits=S) for p, s in zip(pools, sids)], "query B %d S=%d" % (nq, S))
+    # batched step (append on the second session, queries on the first) and a question batch
+    counts = [700, 40]
+    cu = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    q, k, v = [dev(t) for t in synth.draw_qkv(gen, int(cu[-1]), shape)]
+    for rep in range(2):
+        same([p.sk_batch_step([s[1], s[0]], [sk.SK_OP_APPEND, sk.SK_OP_QUERY_B], cu, q, k, v) for p, s in zip(pools, sids)],
+             "batch step %d" % rep)
+    assert pools[3].sk_pool_last_launch()["fused_merge"] == 1
+    P, NQ, Sfx = 16, 8, 8
+    qp, kp, vp = [dev(t) for t in synth.draw_qkv(gen, P, shape)]
+    qs, ks, vs = [dev(t.reshape(NQ, Sfx, t.shape[1], shape.head_dim)) for t in synth.draw_qkv(gen, NQ * Sfx, shape)]
+    same([p.sk_session_query_shared_prefix(s[0], qp, kp, vp, qs, ks, vs) for p, s in zip(pools, sids)], "question batch")
+    torch.cuda.synchronize()
+    for p in pools:
+        p.close()

@@ -20,7 +20,7 @@ OPS = [sk.SK_OP_APPEND, sk.SK_OP_QUERY_A, sk.SK_OP_QUERY_B]
 
 
 def _rows(rng, n_tok, shape, count):
-    return _sample_rows(rng, n_tok, shape.n_q_heads, count, always=[(0, 0), (n_tok - 1, shape.n_q_heads - 1)])
+    return _sample_rows(rng, n_tok, shape, extra=count)
 
 
 def _build(pool, sid, ref, n, shape, gen):

@@ -280,3 +280,163 @@ def test_append_into_a_shared_block_takes_a_copy_first():
     for s in (a, b, c):
         p.sk_session_destroy(s)
     assert p.sk_pool_blocks_free() == 8
+
+
+# ---- a call that fails half way leaves the pool as it was (Alg. 1: an append is one step) ----
+
+def _state(p, sids):
+    return ([(p.sk_session_length(s), p.sk_session_block_table(s)) for s in sids], p.sk_pool_blocks_free())
+
+
+def _grow_to_next_blocks(p, sid, n_tokens):
+    """Blocks the next n_tokens-token append of `sid` would take, read off a run that is then undone."""
+    before = p.sk_session_block_table(sid)
+    n0 = p.sk_session_length(sid)
+    p.reserve(sid, n_tokens)
+    got = p.sk_session_block_table(sid)[len(before):]
+    p.sk_session_truncate(sid, n0)
+    return got
+
+
+SITES_APPEND = [sk.SK_SITE_SCATTER, sk.SK_SITE_ATTENTION]
+
+
+@pytest.mark.parametrize("site", SITES_APPEND + [sk.SK_SITE_RING, sk.SK_SITE_UPLOAD])
+def test_append_that_fails_late_changes_nothing(site):
+    """Every failure site of an append, forced by the test hook on a metadata-only pool (which walks
+    the same steps without the HIP calls): status is an error, lengths, block tables and the number
+    and ORDER of free blocks are as before (the next append gets the blocks it would have got)."""
+    long_list = site in (sk.SK_SITE_RING, sk.SK_SITE_UPLOAD)      # only a list too long for the kernel arguments is uploaded
+    L = 16 * 100 if long_list else 40
+    p, twin = (meta_pool(n_blocks=400, max_batch_tokens=2048) for _ in range(2))
+    for q in (p, twin):
+        q.sk_pool_set_alloc_order(list(range(399, -1, -1)))
+        a, b = q.sk_session_create(), q.sk_session_create()
+        q.reserve(a, 21); q.reserve(b, 5)
+    before = _state(p, [a, b])
+    p.sk_pool_inject_failure(site, 1)
+    with pytest.raises(sk.SkError) as e:
+        p.reserve(a, L)
+    assert e.value.status == sk.SK_E_HIP
+    assert _state(p, [a, b]) == before
+    # the hook is spent: the same call now succeeds and takes exactly the blocks the twin's takes
+    p.reserve(a, L); twin.reserve(a, L)
+    assert _state(p, [a, b]) == _state(twin, [a, b])
+
+
+def test_append_into_a_shared_tail_that_fails_late_keeps_or_returns_the_copy():
+    """A session whose last block is shared with a fork gets a copy of it before it appends.  If the
+    call fails before the commit kernel is enqueued the copy is given back (nothing changed at all);
+    if it fails after, the device block table already names the copy, so the session keeps it: its
+    length and every other block are as before, and one block fewer is free."""
+    for site, keeps_copy in ((sk.SK_SITE_BLOCK_COPY, False), (sk.SK_SITE_SCATTER, False), (sk.SK_SITE_ATTENTION, True)):
+        p = meta_pool(n_blocks=32)
+        a = p.sk_session_create()
+        p.reserve(a, 40)                       # blocks 0,1,2; 8 tokens in block 2
+        f = p.sk_session_fork(a, 40)           # f gets its own copy of block 2 (block 3)
+        p.sk_session_truncate(f, 20)           # f now ends inside block 1, which a also holds
+        before = _state(p, [a, f])
+        p.sk_pool_inject_failure(site, 1)
+        with pytest.raises(sk.SkError):
+            p.reserve(f, 30)
+        after = _state(p, [a, f])
+        assert after[0][0] == before[0][0]                         # the source session never changes
+        assert after[0][1][0] == before[0][1][0]                   # same length for f
+        if keeps_copy:
+            assert after[1] == before[1] - 1
+            assert after[0][1][1][:-1] == before[0][1][1][:-1] and after[0][1][1][-1] != before[0][1][1][-1]
+        else:
+            assert after == before
+        p.reserve(f, 30)                       # and the append still works afterwards
+        assert p.sk_session_length(f) == 50 and p.sk_session_length(a) == 40
+
+
+@pytest.mark.parametrize("site", [sk.SK_SITE_PLAN, sk.SK_SITE_RING, sk.SK_SITE_UPLOAD, sk.SK_SITE_SCATTER, sk.SK_SITE_ATTENTION])
+def test_batch_step_that_fails_late_changes_no_session(site):
+    """A multi-session step that is stopped after some (or all) of its appends were booked - the lists
+    do not fit, the upload slot, the upload, a launch - takes every one of them back, in order."""
+    import ctypes
+    p, twin = (meta_pool(n_blocks=200, max_sessions=6, max_batch_tokens=4096) for _ in range(2))
+    sids = None
+    for q in (p, twin):
+        sids = [q.sk_session_create() for _ in range(5)]
+        for i, s in enumerate(sids):
+            q.reserve(s, 7 + 13 * i)
+    ops = [sk.SK_OP_APPEND, sk.SK_OP_QUERY_B, sk.SK_OP_APPEND, sk.SK_OP_QUERY_A, sk.SK_OP_APPEND]
+    counts = [100, 9, 33, 5, 260]
+    cu = [0]
+    for c in counts:
+        cu.append(cu[-1] + c)
+
+    def step(q):
+        n = len(sids)
+        return sk.lib().sk_batch_step(q.h, n, (ctypes.c_int32 * n)(*sids), (ctypes.c_int32 * n)(*ops),
+                                      (ctypes.c_int32 * (n + 1))(*cu), None, None, None, None, sk.SK_F32, None, None)
+
+    before = _state(p, sids)
+    p.sk_pool_inject_failure(site, 1)
+    rc = step(p)
+    assert rc == (sk.SK_E_WORKSPACE if site == sk.SK_SITE_PLAN else sk.SK_E_HIP)
+    assert _state(p, sids) == before
+    assert step(p) == sk.SK_OK and step(twin) == sk.SK_OK
+    assert _state(p, sids) == _state(twin, sids)
+    assert [p.sk_session_length(s) for s in sids] == [7 + 100, 20, 33 + 33, 46, 59 + 260]
+
+
+def test_batch_step_too_large_for_the_upload_region_is_refused_up_front():
+    """Thousands of one-token items need more list space than a small pool's region holds at the finest
+    decomposition; the planner coarsens it until it fits, and a step that cannot fit is refused with
+    every session unchanged (here the region is sized from max_batch_tokens, so it always fits)."""
+    import ctypes
+    n = 3000
+    p = meta_pool(n_blocks=4096, max_sessions=n, max_batch_tokens=4096, block_tokens=16)
+    sids = [p.sk_session_create() for _ in range(n)]
+    for s in sids:
+        p.reserve(s, 3)
+    cu = list(range(n + 1))
+    ops = [sk.SK_OP_APPEND] * n
+    rc = sk.lib().sk_batch_step(p.h, n, (ctypes.c_int32 * n)(*sids), (ctypes.c_int32 * n)(*ops),
+                                (ctypes.c_int32 * (n + 1))(*cu), None, None, None, None, sk.SK_F32, None, None)
+    assert rc == sk.SK_OK
+    assert all(p.sk_session_length(s) == 4 for s in sids[:50])
+
+
+@pytest.mark.parametrize("site", [sk.SK_SITE_RING, sk.SK_SITE_UPLOAD])
+def test_evict_that_fails_changes_nothing(site):
+    p = meta_pool(n_blocks=64)
+    a = p.sk_session_create()
+    p.reserve(a, 200)
+    p.sk_session_freeze(a, 20)
+    before = _state(p, [a])
+    p.sk_pool_inject_failure(site, 1)
+    with pytest.raises(sk.SkError):
+        p.sk_session_evict_oldest(a, 100)          # frees whole blocks: the device table would be rewritten
+    assert _state(p, [a]) == before
+    p.sk_session_evict_oldest(a, 100)
+    assert p.sk_session_length(a) == 100
+    assert p.sk_pool_blocks_free() > before[1]
+
+
+@pytest.mark.parametrize("site", [sk.SK_SITE_RING, sk.SK_SITE_UPLOAD, sk.SK_SITE_BLOCK_COPY])
+def test_fork_that_fails_changes_nothing(site):
+    p = meta_pool(n_blocks=64, max_sessions=3)
+    a = p.sk_session_create()
+    p.reserve(a, 70)
+    before = _state(p, [a])
+    p.sk_pool_inject_failure(site, 1)
+    with pytest.raises(sk.SkError):
+        p.sk_session_fork(a, 41)                   # ends inside a block: table upload + one block copy
+    assert _state(p, [a]) == before
+    f = p.sk_session_fork(a, 41)                   # the session id was not consumed either
+    g = p.sk_session_create()
+    assert sorted([a, f, g]) == [0, 1, 2]
+    assert p.sk_session_length(f) == 41 and p.sk_pool_blocks_free() == before[1] - 1
+
+
+def test_table_offsets_must_fit_32_bits():
+    """max_sessions x blocks per session is the extent of the device block tables, addressed with
+    32-bit offsets: a description beyond that is refused instead of overflowing."""
+    ok = sk.make_desc("bf16", 32, 8, 128, 16, 1 << 20, max_sessions=2047)
+    bad = sk.make_desc("bf16", 32, 8, 128, 16, 1 << 20, max_sessions=2048)
+    assert sk.sk_pool_workspace_bytes(ok) > 0
+    assert sk.sk_pool_workspace_bytes(bad) == 0
