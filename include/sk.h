@@ -265,6 +265,22 @@ int sk_top2(const float* logits, int32_t rows, int32_t vocab, int64_t row_stride
             void* workspace, size_t workspace_bytes,
             int32_t* idx1, int32_t* idx2, float* val1, float* val2, float* gap, void* hip_stream);
 
+/*
+ * sk_top2 for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without the
+ * workspace, same kernels, same results bit for bit.  The first-pass pairs go to a fixed array
+ * inside the library's device image instead (SK_TOP2_STATIC_BYTES, held by every GPU the library
+ * runs on until the process ends), so rows * ceil(vocab / 8192) * 16 bytes must not exceed that:
+ * otherwise SK_E_WORKSPACE, and nothing is launched.  The call allocates nothing and frees nothing.
+ * The array's device address is looked up once per device, on the first call there (with that
+ * device current); a call with rows == 0 does only that, so a caller can get it out of the way
+ * before a capture.  Every call on a GPU uses that GPU's one array: calls that overlap in time on
+ * one GPU (two streams, two threads) race and must be ordered by the caller; nothing in the array
+ * needs clearing between calls (the first pass writes every entry the second reads).
+ */
+enum { SK_TOP2_STATIC_BYTES = 1 << 20 };
+int sk_top2_static(const float* logits, int32_t rows, int32_t vocab, int64_t row_stride,
+                   int32_t* idx1, int32_t* idx2, float* val1, float* val2, float* gap, void* hip_stream);
 
 /* Byte offset inside kv_mem of element (block, kv_head, is_v, slot, dim), so a harness can
  * address the pool without knowing the layout.  Negative on bad arguments. */

@@ -16,6 +16,7 @@ SK_OP_APPEND, SK_OP_QUERY_A, SK_OP_QUERY_B = 0, 1, 2
 SK_POOL_METADATA_ONLY = 1
 
 SK_SITE_RING, SK_SITE_UPLOAD, SK_SITE_BLOCK_COPY, SK_SITE_SCATTER, SK_SITE_ATTENTION, SK_SITE_COMBINE, SK_SITE_PLAN = 1, 2, 3, 4, 5, 6, 7
+SK_TOP2_STATIC_BYTES = 1 << 20
 
 SK_OK = 0
 SK_E_INVAL, SK_E_SHAPE, SK_E_DTYPE, SK_E_NOMEM, SK_E_BADSESSION = -1, -2, -3, -4, -5
@@ -67,7 +68,7 @@ EXPORTS = [
     "sk_session_truncate", "sk_session_freeze", "sk_session_evict_oldest", "sk_session_fork",
     "sk_pool_set_profiling", "sk_pool_read_profile",
     "sk_pool_element_offset", "sk_pool_get_stats", "sk_pool_last_launch", "sk_strerror",
-    "sk_last_hip_error", "sk_version", "sk_top2_workspace_bytes", "sk_top2",
+    "sk_last_hip_error", "sk_version", "sk_top2_workspace_bytes", "sk_top2", "sk_top2_static",
     "sk_pool_inject_failure",
 ]
 
@@ -113,6 +114,7 @@ def lib():
     L.sk_top2_workspace_bytes.restype = ctypes.c_size_t
     L.sk_top2_workspace_bytes.argtypes = [i32, i32]
     L.sk_top2.argtypes = [vp, i32, i32, i64, vp, ctypes.c_size_t, vp, vp, vp, vp, vp, vp]
+    L.sk_top2_static.argtypes = [vp, i32, i32, i64, vp, vp, vp, vp, vp, vp]
     L.sk_pool_inject_failure.argtypes = [vp, i32, i32]
     L.sk_pool_set_profiling.argtypes = [vp, ctypes.c_int]
     L.sk_pool_read_profile.argtypes = [vp, P(sk_profile), P(ctypes.c_float), P(ctypes.c_float), i32]
@@ -366,6 +368,20 @@ def top2_outputs(rows, device):
     idx1 = torch.empty(rows, dtype=torch.int32, device=device)
     val1 = torch.empty(rows, dtype=torch.float32, device=device)
     return idx1, torch.empty_like(idx1), val1, torch.empty_like(val1), torch.empty_like(val1)
+
+
+def sk_top2_static(logits, outputs=None, stream=None):
+    """sk_top2 through the entry point that allocates nothing: `outputs` (see top2_outputs) are the
+    caller's; they are only made here when left out."""
+    assert logits.is_cuda and logits.dtype == torch.float32 and logits.dim() == 2 and logits.stride(1) == 1
+    rows, vocab = logits.shape
+    if outputs is None:
+        outputs = top2_outputs(rows, logits.device)
+    idx1, idx2, val1, val2, gap = outputs
+    _ck(lib().sk_top2_static(ctypes.c_void_p(logits.data_ptr()) if rows else None, rows, vocab,
+                             logits.stride(0) if rows else vocab, _p(idx1), _p(idx2), _p(val1), _p(val2), _p(gap),
+                             _stream(stream)), "sk_top2_static")
+    return outputs
 
 
 def sk_top2(logits, stream=None, workspace=None, outputs=None):

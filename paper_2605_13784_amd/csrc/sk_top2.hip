@@ -4,7 +4,12 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <limits.h>
+#include <mutex>
 #include "../../include/sk.h"
+
+// First-pass pairs of sk_top2_static: part of the device image, so no call ever allocates it.  In
+// host code this name is only a handle for hipGetSymbolAddress; kernels get the address it returns.
+static __device__ __align__(256) unsigned char scratch[SK_TOP2_STATIC_BYTES];
 
 namespace {
 
@@ -149,6 +154,37 @@ int sk_top2(const float* logits, int32_t rows, int32_t vocab, int64_t row_stride
     hipLaunchKernelGGL(sk_top2_partial, dim3(n_chunks, rows), dim3(256), 0, st, logits, row_stride, vocab, n_chunks, (Top2*)workspace);
     hipLaunchKernelGGL(sk_top2_final, dim3(rows), dim3(256), 0, st, (const Top2*)workspace, n_chunks, idx1, idx2, val1, val2, gap);
     return hipGetLastError() == hipSuccess ? SK_OK : SK_E_HIP;
+}
+
+// Device address of `scratch` on the current device, looked up once per device.
+static int static_scratch(void** out)
+{
+    constexpr int kMaxDevices = 64;
+    static void* ptr_of[kMaxDevices];
+    static std::mutex mu;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SK_E_HIP;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr_of[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SK_E_HIP;
+        ptr_of[dev] = ptr;
+    }
+    *out = ptr_of[dev];
+    return SK_OK;
+}
+
+int sk_top2_static(const float* logits, int32_t rows, int32_t vocab, int64_t row_stride,
+                   int32_t* idx1, int32_t* idx2, float* val1, float* val2, float* gap, void* hip_stream)
+{
+    if (rows < 0 || vocab < 2 || row_stride < vocab) return SK_E_INVAL;
+    void* ptr = nullptr;
+    const int rc = static_scratch(&ptr);
+    if (rc != SK_OK) return rc;
+    if (rows == 0) return SK_OK;
+    if (rows > 65535) return SK_E_INVAL;
+    if (sk_top2_workspace_bytes(rows, vocab) > (size_t)SK_TOP2_STATIC_BYTES) return SK_E_WORKSPACE;
+    return sk_top2(logits, rows, vocab, row_stride, ptr, (size_t)SK_TOP2_STATIC_BYTES, idx1, idx2, val1, val2, gap, hip_stream);
 }
 
 }  // extern "C"
