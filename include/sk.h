@@ -115,13 +115,15 @@ size_t sk_pool_workspace_bytes(const sk_pool_desc* desc);
  *   SK_NO_PACK=1       a question batch gives every question a row tile of its own
  *   SK_NO_INTERLEAVE=1 the splits of a query take contiguous chunks of the cache instead of
  *                      interleaved 64-key pieces
- *   SK_NO_FUSE=1       single-session calls merge their split partials in a second kernel instead
- *                      of inside the attention kernel (the same function merges a row either way:
- *                      the results are bit-identical)
- *   SK_WAIT_POLLS=n    how many polls (about 1 us each) a workgroup of a single-session call waits
- *                      for the other workgroups of its row tile before it leaves the merge to the
- *                      last one (default 256; 0: never wait)
- *   SK_FUSE_LIST=1     batched calls merge inside the attention kernel too (last workgroup only) */
+ *   SK_FUSE=1          single-session calls merge their split partials inside the attention kernel
+ *                      instead of in a second kernel (one launch per call; measured slower on
+ *                      MI355X, so not the default; the same function merges a row either way, the
+ *                      results are bit-identical)
+ *   SK_WAIT_POLLS=n    with SK_FUSE: how many polls a workgroup waits for the other workgroups
+ *                      of its row tile before it leaves the merge to the last one (default 256;
+ *                      0: never wait)
+ *   SK_FUSE_LIST=1     batched calls merge inside the attention kernel (last workgroup only)
+ *   SK_MERGE_FENCES=1  with SK_FUSE: full device-scope fences around the arrival (for comparison) */
 int sk_pool_create(const sk_pool_desc* desc, sk_pool** out);
 /* Frees host metadata and the staging ring; caller memory is untouched.  The caller must
  * have synchronised the stream(s) the pool was used on. */
@@ -318,6 +320,22 @@ typedef struct sk_profile {
 int sk_pool_set_profiling(sk_pool* pool, int enable);
 int sk_pool_read_profile(sk_pool* pool, sk_profile* out, float* attention_ms_per_call /*HOST or NULL*/,
                          float* combine_ms_per_call /*HOST or NULL*/, int32_t capacity);
+
+/*
+ * Measurement probes (benchmarks only; the attention path does not call them).
+ * sk_probe_read: a plain streaming read of `bytes` bytes at src (DEVICE, 16-byte aligned) by
+ * n_workgroups workgroups of 256 threads, 16 bytes per load; the time it takes is the floor of
+ * anything that has to read that many bytes once (Sec. 3.2: a query reads the cache once).
+ * sk_probe_mfma: n_workgroups workgroups of eight waves, each wave `iters` rounds of eight bf16
+ * 32x32x16 matrix products on register operands, read once from `operands` (DEVICE, bf16 data of
+ * the caller's choice, operand_bytes >= 64, 16-byte aligned; the rate the pipe sustains depends on
+ * how much the operand bits toggle) or, with operands NULL, made up in the kernel; *flops_out
+ * (HOST, optional) receives the floating-point operations of the launch.  sink: DEVICE, 4 bytes,
+ * in practice never written.
+ */
+int sk_probe_read(const void* src, size_t bytes, int32_t n_workgroups, void* sink, void* hip_stream);
+int sk_probe_mfma(int32_t n_workgroups, int32_t iters, const void* operands, size_t operand_bytes, void* sink,
+                  double* flops_out, void* hip_stream);
 
 /*
  * Test hook for the error paths: the countdown-th time the pool reaches `site` from now on, that

@@ -5,7 +5,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libsk.so")
-SOURCES = ["sk_kernels.hip", "sk_top2.hip", "sk_pool.cpp"]
+SOURCES = ["sk_kernels.hip", "sk_top2.hip", "sk_probe.hip", "sk_pool.cpp"]
 HEADERS = ["sk_internal.h", os.path.join("..", "..", "include", "sk.h")]
 
 HIPCC_FLAGS = [

@@ -69,7 +69,7 @@ EXPORTS = [
     "sk_pool_set_profiling", "sk_pool_read_profile",
     "sk_pool_element_offset", "sk_pool_get_stats", "sk_pool_last_launch", "sk_strerror",
     "sk_last_hip_error", "sk_version", "sk_top2_workspace_bytes", "sk_top2", "sk_top2_static",
-    "sk_pool_inject_failure",
+    "sk_pool_inject_failure", "sk_probe_read", "sk_probe_mfma",
 ]
 
 _lib = None
@@ -116,6 +116,8 @@ def lib():
     L.sk_top2.argtypes = [vp, i32, i32, i64, vp, ctypes.c_size_t, vp, vp, vp, vp, vp, vp]
     L.sk_top2_static.argtypes = [vp, i32, i32, i64, vp, vp, vp, vp, vp, vp]
     L.sk_pool_inject_failure.argtypes = [vp, i32, i32]
+    L.sk_probe_read.argtypes = [vp, ctypes.c_size_t, i32, vp, vp]
+    L.sk_probe_mfma.argtypes = [i32, i32, vp, ctypes.c_size_t, vp, P(ctypes.c_double), vp]
     L.sk_pool_set_profiling.argtypes = [vp, ctypes.c_int]
     L.sk_pool_read_profile.argtypes = [vp, P(sk_profile), P(ctypes.c_float), P(ctypes.c_float), i32]
     L.sk_pool_element_offset.restype = i64
@@ -396,3 +398,19 @@ def sk_top2(logits, stream=None, workspace=None, outputs=None):
     _ck(lib().sk_top2(ctypes.c_void_p(logits.data_ptr()) if rows else None, rows, vocab, logits.stride(0) if rows else vocab, _p(workspace),
                       workspace.numel(), _p(idx1), _p(idx2), _p(val1), _p(val2), _p(gap), _stream(stream)), "sk_top2")
     return idx1, idx2, val1, val2, gap
+
+
+def sk_probe_read(buf, n_workgroups, sink, stream=None, nbytes=None):
+    """Plain streaming read of a CUDA tensor (measurement probe)."""
+    nbytes = buf.numel() * buf.element_size() if nbytes is None else int(nbytes)
+    _ck(lib().sk_probe_read(_p(buf), nbytes, int(n_workgroups), _p(sink), _stream(stream)), "sk_probe_read")
+
+
+def sk_probe_mfma(n_workgroups, iters, sink, operands=None, stream=None):
+    """Back-to-back bf16 matrix products on register operands (measurement probe), the operands taken
+    from the bf16 CUDA tensor `operands` if given; returns the flops of the launch."""
+    f = ctypes.c_double()
+    nb = 0 if operands is None else operands.numel() * operands.element_size()
+    _ck(lib().sk_probe_mfma(int(n_workgroups), int(iters), _p(operands), nb, _p(sink), ctypes.byref(f), _stream(stream)),
+        "sk_probe_mfma")
+    return f.value

@@ -116,7 +116,8 @@ struct sk_launch {
     // s + 2S, .. of the cache instead of one contiguous chunk, so that the workgroups of a head walk
     // through memory side by side instead of as S separate streams (the host decides when)
     int32_t interleave;
-    // In-kernel merge of the split partials.  sync holds two counters per unit, both zero between
+    // In-kernel merge of the split partials (optional; the default is the combine kernel, which
+    // measured faster).  sync holds two counters per unit, both zero between
     // launches: arrivals (low 16 bits; the high bits count workgroups that gave up waiting) and
     // departures.  A workgroup writes its partial, arrives, and waits up to wait_polls polls for the
     // others; then every workgroup of the unit merges its own share of the rows.  One that gives up
@@ -125,6 +126,8 @@ struct sk_launch {
     uint32_t* sync;
     int32_t fuse;
     int32_t wait_polls;
+    int32_t merge_fences;   // 1: full device-scope fences around the arrival (slow: an L2 walk each); 0: see the kernel
+    int32_t pad2;
 };
 
 // Launchers implemented in sk_kernels.hip (return hipError_t as int).

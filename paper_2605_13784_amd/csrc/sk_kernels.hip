@@ -137,49 +137,80 @@ __device__ __forceinline__ const unsigned char* sk_group_base(const sk_seg& g, i
 // One wave merges the split partials of one output row (partial row prow0 of the first split, the
 // others pstride rows apart):
 //   M = max_s m_s ; w_s = 2^(m_s - M) ; O = sum_s O_s w_s / sum_s l_s w_s ; LSE = (M + log2 sum_s lx_s w_s) ln 2
-// Lane s holds the statistics of split s, every lane two (d = 128) or one (d = 64) output dimensions.
-// The splits are added in index order whoever calls this (the combine kernel, or a workgroup of the
-// attention kernel), so the result depends on the partials only.  Up to 32 splits are read with one
-// memory round trip: every load is issued before the first value is used.
+// Lane s holds the statistics of splits s, s + 64, ..; every lane two output dimensions (one when
+// d = 64).  The splits are added in index order whoever calls this (the combine kernel, or a
+// workgroup of the attention kernel), with explicit FMAs, so the result depends on the partials only.
+// Rows are read BATCH splits at a time, the next batch requested before the current one is used.
+// COHERENT: the partials were written by other workgroups of the same launch (with write-through
+// stores); they are read with device-scope loads, which see them wherever the reader runs, so the
+// reader needs no cache invalidate (measured at over 10 us when every workgroup issues one).
+template <bool COHERENT>
+__device__ __forceinline__ float sk_ld_partial(const float* p)
+{
+    if (COHERENT) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return *p;
+}
+
+template <bool COHERENT, int BATCH>
 __device__ __forceinline__ void sk_merge_row(const sk_launch& P, const size_t prow0, const size_t pstride, const int n_parts,
                                              const size_t orow, const int lane)
 {
     const int d = P.g.d;
-    const int per_lane = d >> 6;     // 1 (d=64) or 2 (d=128)
-    const float* obase = P.part_o + prow0 * d + per_lane * lane;
+    const bool two = d == 128;
+    // dimensions of a lane: COHERENT (32-bit loads) lane and lane + 64; else (64-bit loads) 2 lane, 2 lane + 1
+    const int d0 = COHERENT ? lane : (two ? 2 * lane : lane);
+    const int d1 = COHERENT ? lane + 64 : 2 * lane + 1;
+    const float* obase = P.part_o + prow0 * d + d0;
     const size_t ostride = pstride * d;
-    const float4* mlbase = (const float4*)P.part_ml + prow0;
+    const float* mlbase = P.part_ml + prow0 * 4;
+    const size_t mlstride = pstride * 4;
+    auto load_o = [&](const int s, float& x0, float& x1) __attribute__((always_inline)) {
+        const float* op = obase + (size_t)s * ostride;
+        if (COHERENT) { x0 = sk_ld_partial<true>(op); x1 = two ? sk_ld_partial<true>(op + 64) : 0.f; }
+        else if (two) { const float2 t = *(const float2*)op; x0 = t.x; x1 = t.y; }
+        else { x0 = *op; x1 = 0.f; }
+    };
     float M = SK_NEG_INF;
-    if (n_parts > 32) {              // rare: the maximum needs its own pass
-        for (int s = lane; s < n_parts; s += 64) M = fmaxf(M, mlbase[(size_t)s * pstride].x);
+    if (n_parts > 64) {              // rare: the maximum needs its own pass
+        for (int s = lane; s < n_parts; s += 64) M = fmaxf(M, sk_ld_partial<COHERENT>(mlbase + (size_t)s * mlstride));
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
     }
     float L = 0.f, Lx = 0.f, a0 = 0.f, a1 = 0.f;
-    for (int base = 0; base < n_parts; base += 32) {
-        const int cnt = n_parts - base < 32 ? n_parts - base : 32;
-        float2 x[32];
+    for (int base = 0; base < n_parts; base += 64) {
+        const int cnt = n_parts - base < 64 ? n_parts - base : 64;
+        float x0[BATCH], x1[BATCH], y0[BATCH], y1[BATCH];
 #pragma unroll
-        for (int j = 0; j < 32; ++j) {
-            x[j] = make_float2(0.f, 0.f);
-            if (j < cnt) {
-                const float* op = obase + (size_t)(base + j) * ostride;
-                if (per_lane == 2) x[j] = *(const float2*)op; else x[j].x = *op;
-            }
+        for (int j = 0; j < BATCH; ++j) {
+            x0[j] = 0.f; x1[j] = 0.f;
+            if (j < cnt) load_o(base + j, x0[j], x1[j]);
         }
-        float4 ml = make_float4(SK_NEG_INF, 0.f, 0.f, 0.f);
-        if (lane < cnt) ml = mlbase[(size_t)(base + lane) * pstride];
-        if (n_parts <= 32) {
-            M = ml.x;
+        float m_s = SK_NEG_INF, l_s = 0.f, lx_s = 0.f;
+        if (lane < cnt) {
+            const float* mp = mlbase + (size_t)(base + lane) * mlstride;
+            if (COHERENT) { m_s = sk_ld_partial<true>(mp); l_s = sk_ld_partial<true>(mp + 1); lx_s = sk_ld_partial<true>(mp + 2); }
+            else { const float4 t = *(const float4*)mp; m_s = t.x; l_s = t.y; lx_s = t.z; }
+        }
+        if (n_parts <= 64) {
+            M = m_s;
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
         }
-        const float wgt = (ml.x == SK_NEG_INF) ? 0.f : sk_exp2(ml.x - M);
-        L = fmaf(ml.y, wgt, L); Lx = fmaf(ml.z, wgt, Lx);      // explicit FMAs: every copy of this function rounds alike
+        const float wgt = (m_s == SK_NEG_INF) ? 0.f : sk_exp2(m_s - M);
+        L = fmaf(l_s, wgt, L); Lx = fmaf(lx_s, wgt, Lx);
+        for (int j0 = 0; j0 < cnt; j0 += BATCH) {
 #pragma unroll
-        for (int j = 0; j < 32; ++j) {
-            const float wj = __shfl(wgt, j, 64);         // 0 for splits past the end
-            a0 = fmaf(x[j].x, wj, a0); a1 = fmaf(x[j].y, wj, a1);
+            for (int j = 0; j < BATCH; ++j) {           // request the next batch
+                y0[j] = 0.f; y1[j] = 0.f;
+                if (j0 + BATCH + j < cnt) load_o(base + j0 + BATCH + j, y0[j], y1[j]);
+            }
+#pragma unroll
+            for (int j = 0; j < BATCH; ++j) {
+                const float wj = __shfl(wgt, j0 + j, 64);    // 0 for splits past the end
+                a0 = fmaf(x0[j], wj, a0); a1 = fmaf(x1[j], wj, a1);
+            }
+#pragma unroll
+            for (int j = 0; j < BATCH; ++j) { x0[j] = y0[j]; x1[j] = y1[j]; }
         }
     }
 #pragma unroll
@@ -187,12 +218,12 @@ __device__ __forceinline__ void sk_merge_row(const sk_launch& P, const size_t pr
     const float inv = 1.0f / L;
     if (P.out_dtype == 0) {
         float* o = (float*)P.out + orow * d;
-        if (per_lane == 2) *(float2*)(o + 2 * lane) = make_float2(a0 * inv, a1 * inv);
-        else o[lane] = a0 * inv;
+        if (COHERENT || !two) { o[d0] = a0 * inv; if (two) o[d1] = a1 * inv; }
+        else *(float2*)(o + d0) = make_float2(a0 * inv, a1 * inv);
     } else {
         uint16_t* o = (uint16_t*)P.out + orow * d;
-        if (per_lane == 2) *(uint32_t*)(o + 2 * lane) = f32_to_bf16_bits(a0 * inv) | ((uint32_t)f32_to_bf16_bits(a1 * inv) << 16);
-        else o[lane] = f32_to_bf16_bits(a0 * inv);
+        if (COHERENT || !two) { o[d0] = f32_to_bf16_bits(a0 * inv); if (two) o[d1] = f32_to_bf16_bits(a1 * inv); }
+        else *(uint32_t*)(o + d0) = f32_to_bf16_bits(a0 * inv) | ((uint32_t)f32_to_bf16_bits(a1 * inv) << 16);
     }
     if (P.lse && lane == 0) P.lse[orow] = (M + sk_log2(Lx)) * SK_LN2;
 }
@@ -266,6 +297,18 @@ __device__ __forceinline__ void sk_dma16(const void* base, unsigned lane_off, un
 {   // address = base (scalar registers) + lane_off (one VGPR, unsigned)
     asm volatile("s_add_u32 m0, %0, %3\n\tglobal_load_lds_dwordx4 %1, %2"
                  : : "s"(lds_addr), "v"(lane_off), "s"(base), "n"(IMM) : "memory", "m0", "scc");
+}
+
+// 16-byte store that is written through to memory at once (cache policy "system coherent"), so that
+// the split partials never sit as dirty lines in one XCD's L2: the workgroups that merge them may run
+// on another XCD, and a release fence wide enough for that would have to walk the whole L2 for dirty
+// lines (measured: about 25 us per kernel).  Written as inline assembly (the compiler has no store
+// with these bits outside atomics), so the caller waits for it by hand (SK_WAIT_VMCNT(0)).
+typedef __attribute__((ext_vector_type(4))) float sk_f32x4;
+__device__ __forceinline__ void sk_store16_through(float* p, const float4 v)
+{
+    const sk_f32x4 x = {v.x, v.y, v.z, v.w};
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(p), "v"(x) : "memory");
 }
 
 // Pool blocks holding the two 16-key groups of the tile that starts at key t0 (scalar loads).
@@ -441,8 +484,8 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
         };
 
         // S^T = K Q^T, TPW independent accumulator chains
-        auto step_scores = [&](auto stage_const) __attribute__((always_inline)) {
-            constexpr int STAGE = decltype(stage_const)::value;
+        // (`soff`: byte offset of the ring slot read, a constant when the loop is unrolled over the slots)
+        auto step_scores = [&](const int soff) __attribute__((always_inline)) {
 #pragma unroll
             for (int t = 0; t < TPW; ++t)
 #pragma unroll
@@ -452,7 +495,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
             for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
                 for (int t = 0; t < TPW; ++t)
-                    ka[t][ks] = *(sk_lds_u4ptr)(kptr[ks] + SK_SLOT_OFF(STAGE, t));
+                    ka[t][ks] = *(sk_lds_u4ptr)(kptr[ks] + soff + SK_SLOT_OFF(0, t));
             __builtin_amdgcn_s_setprio(2);     // the wave feeding the matrix pipe goes first
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks)
@@ -464,13 +507,12 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
             __builtin_amdgcn_sched_group_barrier(0x100, 8 * TPW, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 8 * TPW, 0);
         };
-        auto load_v_tile = [&](const int t, auto stage_const) __attribute__((always_inline)) {
-            constexpr int STAGE = decltype(stage_const)::value;
+        auto load_v_tile = [&](const int t, const int soff) __attribute__((always_inline)) {
 #pragma unroll
             for (int q = 0; q < 2; ++q)
 #pragma unroll
                 for (int mt = 0; mt < 4; ++mt)
-                    va[t][q][mt] = *(sk_lds_u4ptr)(vptr[mt] + SK_SLOT_OFF(STAGE, t) + q * 4 * US);
+                    va[t][q][mt] = *(sk_lds_u4ptr)(vptr[mt] + soff + SK_SLOT_OFF(0, t) + q * 4 * US);
         };
         // mask (only tiles that cross a limit), row maximum, P = exp2(s * scale - m), row sums
         auto step_softmax = [&](const int it) __attribute__((always_inline)) {
@@ -577,10 +619,13 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
             for (int p = 0; p < TPI; ++p)
                 nb[p] = sk_lookup_tile(g, g.begin + (NSS - 1) * g.step + p * SK_TILE, last_group);
 
-            // STAGE is the ring slot the iteration reads; the slot read by the previous iteration is
-            // refilled with iteration it + NSS - 1.
-            auto iteration = [&](const int it, auto stage_const) __attribute__((always_inline)) {
-                constexpr int STAGE = decltype(stage_const)::value;
+            // `slot` is the ring slot the iteration reads; the slot read by the previous iteration is
+            // refilled with iteration it + NSS - 1.  With the two-slot ring the loop is unrolled over the
+            // slots (the slot offsets fold into the LDS instructions); a four-slot ring takes the slot at
+            // run time (one copy of the loop body).  The four-wave instances in use have two slots: with
+            // four (three iterations in flight, 128 KiB, one workgroup per CU) a query measured slower
+            // (32 tokens at 32K: 38 against 33 us; 16 tokens at 128K: 103 against 98 us).
+            auto iteration = [&](const int it, const int slot) __attribute__((always_inline)) {
                 // this wave's loads of iteration `it` have landed: everything but the loads of the
                 // (at most NSS - 2) later iterations already issued
                 const int later = niter - 1 - it;
@@ -592,7 +637,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
 #pragma unroll
                     for (int p = 0; p < TPI; ++p)
                         sk_issue_tile<US>(g, g.begin + (it + NSS - 1) * g.step + p * SK_TILE, last_group, nb[p],
-                                                       unit_base + SK_SLOT_OFF((STAGE + NSS - 1) % NSS, p), koff, voff);
+                                                       unit_base + SK_SLOT_OFF((slot + NSS - 1) % NSS, p), koff, voff);
                     if (it + NSS < niter) {
 #pragma unroll
                         for (int p = 0; p < TPI; ++p)
@@ -600,20 +645,21 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
                     }
                 }
                 if (!is_active(it)) return;
-                step_scores(sk_int<STAGE>{});
+                step_scores(slot * 1024);
 #pragma unroll
-                for (int t = 0; t < TPW; ++t) load_v_tile(t, sk_int<STAGE>{});   // requested now: their LDS latency hides behind the softmax
+                for (int t = 0; t < TPW; ++t) load_v_tile(t, slot * 1024);   // requested now: their LDS latency hides behind the softmax
                 step_softmax(it);
 #pragma unroll
                 for (int t = 0; t < TPW; ++t) pv_tile(t);
             };
-            for (int it = 0; it < niter; it += NSS) {
-                iteration(it, sk_int<0>{});
-                if (it + 1 < niter) iteration(it + 1, sk_int<1>{});
-                if (NSS == 4) {
-                    if (it + 2 < niter) iteration(it + 2, sk_int<2>{});
-                    if (it + 3 < niter) iteration(it + 3, sk_int<3>{});
+            if constexpr (NSS == 2) {
+                for (int it = 0; it < niter; it += 2) {
+                    iteration(it, 0);
+                    if (it + 1 < niter) iteration(it + 1, 1);
                 }
+            } else {
+#pragma unroll 1
+                for (int it = 0; it < niter; ++it) iteration(it, it & (NSS - 1));
             }
         } else {
             // ---- eight waves in two groups of four that take turns.  Every wave alternates between
@@ -815,7 +861,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
         const size_t orow_lane = ((size_t)(w.q_tok0 + tok_local) * P.g.Hq + hq);
         if (row_valid && kg == 0) {
             if (direct) { if (P.lse) P.lse[orow_lane] = (m_ref + sk_log2(lx_tot)) * SK_LN2; }
-            else *((float4*)P.part_ml + ((size_t)w.part * P.rows_per_slot + row_in_tile)) = make_float4(m_ref, l_tot, lx_tot, 0.f);
+            else sk_store16_through(P.part_ml + ((size_t)w.part * P.rows_per_slot + row_in_tile) * 4, make_float4(m_ref, l_tot, lx_tot, 0.f));
         }
         const int c4 = lane & 31;
 #pragma unroll
@@ -837,10 +883,11 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
                     *(uint2*)((uint16_t*)P.out + orow * 128 + c4 * 4) = make_uint2(lo, hi);
                 }
             } else {
-                *(float4*)(P.part_o + ((size_t)w.part * P.rows_per_slot + rit) * 128 + c4 * 4) = val;
+                sk_store16_through(P.part_o + ((size_t)w.part * P.rows_per_slot + rit) * 128 + c4 * 4, val);
             }
         }
     }
+    SK_WAIT_VMCNT(0);                                 // the partial's stores (inline assembly) have completed
     if (direct || !P.fuse) return;
 
     // ---- in-kernel merge of the split partials ----
@@ -854,8 +901,13 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
     __syncthreads();                                  // the whole partial is written (and LDS is free again)
     volatile int* flag = (volatile int*)lds;
     uint32_t* cnt = P.sync + 2 * (size_t)w.unit;
+    uint32_t left = 0;
+    // Release: every thread has waited for its write-through stores and passed the barrier above, so
+    // the partial is in memory before the arrival below.  Acquire: the merge reads the partials with
+    // device-scope loads, issued after the counter has said that everybody has arrived (the fence below
+    // only keeps the compiler and this workgroup's waves from reading earlier).
     if (tid == 0) {
-        __threadfence();                              // release: the partial is visible device-wide before the arrival
+        if (P.merge_fences) __threadfence();
         const uint32_t np = (uint32_t)w.n_parts;
         const uint32_t old = __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         int state;                                    // 0: leave, 1: merge the own share, 2: merge every share
@@ -863,7 +915,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
         else {
             state = 0;
             for (int i = 0; i < P.wait_polls; ++i) {
-                __builtin_amdgcn_s_sleep(8);
+                __builtin_amdgcn_s_sleep(4);
                 if ((__hip_atomic_load(cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & 0xffffu) == np) { state = 1; break; }
             }
             if (state == 0) {
@@ -873,7 +925,10 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
                 if ((o2 & 0xffffu) == np) state = 1;
             }
         }
-        __threadfence();                              // acquire: the other partials are read after the counter
+        if (P.merge_fences) __threadfence(); else __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        // departure (this workgroup will not look at the arrival counter again), requested now so that
+        // its round trip runs beside the merge; the answer is needed at the very end only
+        left = __hip_atomic_fetch_add(cnt + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         *flag = state;
     }
     __syncthreads();
@@ -887,13 +942,12 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
             const int row_end = (k + 1) * rps < nrows ? (k + 1) * rps : nrows;
             for (int row = k * rps + wave; row < row_end; row += NW) {
                 const size_t orow = (size_t)(w.q_tok0 + (row >> log2G)) * P.g.Hq + w.kv_head * G + (row & (G - 1));
-                sk_merge_row(P, (size_t)w.part0 * P.rows_per_slot + row, (size_t)P.g.Hkv * P.rows_per_slot, w.n_parts, orow, lane);
+                sk_merge_row<true, 16>(P, (size_t)w.part0 * P.rows_per_slot + row, (size_t)P.g.Hkv * P.rows_per_slot, w.n_parts, orow, lane);
             }
         }
     }
-    // departure: the last workgroup of the unit to get here clears the counters for the next launch
+    // the last workgroup of the unit to depart clears the counters for the next launch
     if (tid == 0) {
-        const uint32_t left = __hip_atomic_fetch_add(cnt + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (left + 1u == (uint32_t)w.n_parts) {
             __hip_atomic_store(cnt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(cnt + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1056,7 +1110,7 @@ __global__ __launch_bounds__(256) void sk_combine(const sk_launch P)
     const int G = P.g.G;
     if (row >= cb.n_tok * G) return;
     const size_t orow = ((size_t)(cb.q_tok0 + row / G) * P.g.Hq + cb.kv_head * G + row % G);
-    sk_merge_row(P, (size_t)cb.part0 * P.rows_per_slot + row, (size_t)cb.part_stride * P.rows_per_slot, cb.n_parts, orow, lane);
+    sk_merge_row<false, 8>(P, (size_t)cb.part0 * P.rows_per_slot + row, (size_t)cb.part_stride * P.rows_per_slot, cb.n_parts, orow, lane);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -138,8 +138,9 @@ struct sk_pool {
     int target_wgs = kDefaultTargetWgs;
     bool target_wgs_set = false;
     bool force_simple = false, no_256 = false, no_pack = false, no_interleave = false;
-    bool fuse = true;                    // single-session calls merge their split partials inside the attention kernel
+    bool fuse = false;                   // SK_FUSE=1: single-session calls merge their split partials inside the attention kernel
     bool fuse_list = false;              // batched calls too (the last workgroup of a unit merges alone)
+    bool merge_fences = false;           // SK_MERGE_FENCES=1: full fences around the arrival (for comparison)
     int wait_polls = kDefaultWaitPolls;
     int n_cus = 256;                     // compute units of the device the pool was created on
     // test hook (sk_pool_inject_failure): the countdown-th arrival at `inject_site` fails
@@ -326,13 +327,16 @@ int plan_regular(const sk_pool* p, int32_t id, int64_t n_tok, int32_t pos0, int6
     // (16 tokens at 128K: 98 / 96 / 92 us with 16- / 64- / 256-token blocks).
     L.interleave = (!p->no_interleave && v.id == SK_KV_MFMA64 && S > 1 && kv_len <= (int64_t)pos0) ? 1 : 0;
     R.base_wgs = (int32_t)base_wgs; R.parts = (int32_t)parts; R.wgs = int32_t(base_wgs * parts); R.kv_len = kv_len;
-    // The matrix-pipe kernels merge their split partials themselves (one launch per call).  Workgroups
-    // only wait for each other when the whole launch fits on the device at once (the 256-row instance
-    // holds a CU alone, the others share it in pairs); otherwise the last workgroup of a unit merges alone.
+    // On request (SK_FUSE=1) the matrix-pipe kernels merge their split partials themselves (one launch per
+    // call).  Workgroups only wait for each other when the whole launch fits on the device at once (the
+    // 256-row instance holds a CU alone, the others share it in pairs); otherwise the last workgroup of a
+    // unit merges alone.  Not the default: a device-scope round trip (atomic, coherent load) measured about
+    // 3 us on this hardware and the scheme needs four in a row, against 6-7 us for the combine kernel.
     const bool mfma = v.id != SK_KV_SIMPLE;
     L.fuse = (p->fuse && mfma && parts > 1 && base_wgs <= p->L.sync_units && parts < 65536) ? 1 : 0;
     const int64_t resident = int64_t(p->n_cus) * (v.id == SK_KV_MFMA256 ? 1 : 2);
     L.wait_polls = (L.fuse && R.wgs <= resident) ? p->wait_polls : 0;
+    L.merge_fences = p->merge_fences ? 1 : 0;
     return SK_OK;
 }
 
@@ -750,6 +754,7 @@ int launch_list(sk_pool* p, ListPlan& P, const ScatterBatch* sb, int n_sb, ListG
         L[gi].comb = (const sk_comb*)(dev_meta + off_comb[gi]);
         L[gi].fuse = P.fuse ? 1 : 0;
         L[gi].wait_polls = 0;          // the workgroups of a long list are not resident together
+        L[gi].merge_fences = p->merge_fences ? 1 : 0;
         int e = sk_launch_attention(L[gi], g.v.id, (int32_t)P.work[gi].size(), st);
         if (e) { g_last_hip = e; return SK_E_HIP; }
         p->stats.launches++;
@@ -832,8 +837,9 @@ int sk_pool_create(const sk_pool_desc* desc, sk_pool** out)
     p->no_256 = env_on("SK_NO_256");
     p->no_pack = env_on("SK_NO_PACK");
     p->no_interleave = env_on("SK_NO_INTERLEAVE");
-    p->fuse = !env_on("SK_NO_FUSE");
+    p->fuse = env_on("SK_FUSE");
     p->fuse_list = env_on("SK_FUSE_LIST");
+    p->merge_fences = env_on("SK_MERGE_FENCES");
     if (const char* t = getenv("SK_WAIT_POLLS")) { int x = atoi(t); if (x >= 0) p->wait_polls = x; }
     if (!meta_only) {
         int dev = 0, cus = 0;

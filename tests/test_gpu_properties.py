@@ -214,17 +214,18 @@ def _pool_with_env(env, shape, **kw):
 
 
 def test_merge_inside_the_kernel_equals_the_separate_combine_bit_for_bit():
-    """The split partials of a call are merged by whichever workgroups happen to do it: all of a row
-    tile's workgroups sharing the rows (they waited for each other), the last one alone (nobody
-    waits: SK_WAIT_POLLS=0), or a second kernel (SK_NO_FUSE=1).  One function merges a row in split
-    order in all three, so outputs and log-sum-exps must agree to the last bit, call after call (the
-    counters the workgroups meet at are left at zero by every launch); also for a batched step and a
-    question batch with SK_FUSE_LIST=1."""
+    """The split partials of a call are merged by a second kernel (the default) or, with SK_FUSE=1, by
+    whichever workgroups of the attention kernel happen to do it: all of a row tile's workgroups
+    sharing the rows (they waited for each other), or the last one alone (nobody waits:
+    SK_WAIT_POLLS=0).  One function merges a row in split order in all of them, so outputs and
+    log-sum-exps must agree to the last bit, call after call (the counters the workgroups meet at are
+    left at zero by every launch); also for a batched step and a question batch with SK_FUSE_LIST=1."""
     shape = synth.CFG2
     gen = synth.generator(2, stream=77)
     kw = dict(block_tokens=16, n_blocks=700, max_sessions=3, max_batch_tokens=2048)
-    pools = [_pool_with_env({}, shape, **kw), _pool_with_env({"SK_WAIT_POLLS": "0"}, shape, **kw),
-             _pool_with_env({"SK_NO_FUSE": "1"}, shape, **kw), _pool_with_env({"SK_FUSE_LIST": "1"}, shape, **kw)]
+    pools = [_pool_with_env({"SK_FUSE": "1"}, shape, **kw), _pool_with_env({"SK_FUSE": "1", "SK_WAIT_POLLS": "0"}, shape, **kw),
+             _pool_with_env({}, shape, **kw), _pool_with_env({"SK_FUSE": "1", "SK_FUSE_LIST": "1"}, shape, **kw),
+             _pool_with_env({"SK_FUSE": "1", "SK_MERGE_FENCES": "1"}, shape, **kw)]
     sids = [(p.sk_session_create(), p.sk_session_create()) for p in pools]
 
     def same(results, what):
