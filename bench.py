@@ -470,7 +470,7 @@ def fp32_small(sk, reps=200):
             "roofline": {"kernel": "sk_attn_simple<false>", "bound": "alu", "achieved": fa / (a_us * 1e-6) / 1e12,
                          "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": fa / (a_us * 1e-6) / 1e12 / FP32_VALU_PEAK_TFLOPS,
                          "traffic": None, "algorithmic_flops": fa,
-                         "note": "1.6e7 flop per call: launch-bound at this size, the fraction says nothing about the kernel"},
+                         "note": "6.5e7 flop per call: launch-bound at this size, the fraction says nothing about the kernel"},
             "query_tflops": fq / (q_us * 1e-6) / 1e12}
 
 
