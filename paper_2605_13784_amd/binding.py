@@ -86,6 +86,9 @@ def lib():
         return _lib
     if not os.path.exists(_build.LIB):
         _build.build(force=True)
+    elif _build.is_stale():
+        import warnings
+        warnings.warn("%s is older than its sources; run paper_2605_13784_amd._build.build()" % _build.LIB, RuntimeWarning)
     L = ctypes.CDLL(_build.LIB)
     vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
     P = ctypes.POINTER
