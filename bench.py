@@ -20,9 +20,9 @@ Every figure comes from this run.  Three kinds of timing are used and named wher
   wall    host clock around a batch of calls bracketed by device synchronisation;
   stream  a pair of HIP events on the launch stream around a batch of back-to-back calls, divided
           by the number of calls (no event between the calls: what a caller issuing them sees);
-  kernel  HIP events recorded by the library right before and after one kernel on its stream
-          (sk_pool_set_profiling), in a repeat of the timed steps; an event pair adds 3-6 us to
-          what rocprofv3 reports for the same launch (profiles/).
+  kernel  the dispatch's own start and end time stamps, which the library has the runtime write into
+          a pair of HIP events per kernel launch (sk_pool_set_profiling), in a repeat of the timed
+          steps: the duration rocprofv3 reports for the same launch (profiles/).
 HBM bytes per dispatch from hardware counters need rocprofv3 around the process and are therefore
 not in this line ("traffic": null); the summaries under profiles/ carry them.
 """

@@ -306,11 +306,13 @@ typedef struct sk_launch_info {
 int sk_pool_last_launch(const sk_pool* pool, sk_launch_info* out);
 
 /*
- * Optional timing of the kernels themselves, for benchmarks: while enabled, every attention
- * call records HIP events on its stream before and after the attention kernel and after the
- * combine kernel.  sk_pool_read_profile waits for the recorded events, returns the sums since
- * the last read (and, if the arrays are given, the first `capacity` calls one by one, in call
- * order, in milliseconds) and clears them.  At most 4096 calls are kept between reads.
+ * Optional timing of the kernels themselves, for benchmarks: while enabled, every attention and
+ * combine kernel is launched with a pair of events that the runtime fills with the dispatch's own
+ * start and end time stamps (what a profiler reports as the kernel's duration; nothing is recorded
+ * on the stream between kernels).  sk_pool_read_profile waits for the recorded events, returns the
+ * sums since the last read (and, if the arrays are given, the first `capacity` calls one by one, in
+ * call order, in milliseconds: the attention kernels of a call added up, and its combine kernels) and
+ * clears them.  At most 16,384 kernel dispatches are kept between reads.
  */
 typedef struct sk_profile {
     int64_t calls;

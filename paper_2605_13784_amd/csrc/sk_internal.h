@@ -137,8 +137,8 @@ int sk_launch_scatter(const sk_geom& g, const void* k, const void* v, const sk_s
 int sk_launch_scatter_args(const sk_geom& g, const void* k, const void* v, const sk_scatter_list& items,
                            int32_t n_items, int32_t* tables_rw, unsigned char* kv_rw,
                            unsigned char* eph_rw, void* stream);
-int sk_launch_attention(const sk_launch& L, int variant, int32_t n_workgroups, void* stream);
-int sk_launch_combine(const sk_launch& L, int32_t n_row_tiles, void* stream);
+int sk_launch_attention(const sk_launch& L, int variant, int32_t n_workgroups, void* stream, void* ev_start, void* ev_stop);
+int sk_launch_combine(const sk_launch& L, int32_t n_row_tiles, void* stream, void* ev_start, void* ev_stop);
 int sk_launch_gather(const sk_geom& g, int32_t tbl_off, int64_t first, int64_t count,
                      void* k_out, void* v_out, void* stream);
 int sk_launch_copy_block(const sk_geom& g, unsigned char* kv_rw, int32_t src, int32_t dst, void* stream);

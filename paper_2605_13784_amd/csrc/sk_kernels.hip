@@ -2,6 +2,7 @@
 // session cache (bf16 MFMA kernel and an fp32 FMA kernel), cross-split log-sum-exp combine,
 // gather.  What they compute is defined in include/sk.h; the data layout in sk_internal.h.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include "sk_internal.h"
 
@@ -1252,27 +1253,38 @@ int sk_launch_scatter_args(const sk_geom& g, const void* k, const void* v, const
     return (int)hipGetLastError();
 }
 
-int sk_launch_attention(const sk_launch& L, int variant, int32_t n_workgroups, void* stream)
+// The two launchers below take an optional pair of events that the runtime fills with the
+// dispatch's own start and end time stamps (the figures a profiler reports for the kernel), for
+// sk_pool_set_profiling; without them they are plain launches.
+#define SK_LAUNCH(kernel, grid, block)                                                                              \
+    do {                                                                                                            \
+        if (ev_start) hipExtLaunchKernelGGL(kernel, grid, block, 0, st, (hipEvent_t)ev_start, (hipEvent_t)ev_stop, 0, L); \
+        else hipLaunchKernelGGL(kernel, grid, block, 0, st, L);                                                     \
+    } while (0)
+
+int sk_launch_attention(const sk_launch& L, int variant, int32_t n_workgroups, void* stream, void* ev_start, void* ev_stop)
 {
     if (n_workgroups <= 0) return 0;
     hipStream_t st = (hipStream_t)stream;
     switch (variant) {
-    case SK_KV_MFMA256:      hipLaunchKernelGGL((sk_attn_bf16_d128<8, 1, 4>), dim3(n_workgroups), dim3(512), 0, st, L); break;
-    case SK_KV_MFMA128:      hipLaunchKernelGGL((sk_attn_bf16_d128<4, 1, 2>), dim3(n_workgroups), dim3(256), 0, st, L); break;
-    case SK_KV_MFMA64:       hipLaunchKernelGGL((sk_attn_bf16_d128<2, 2, 2>), dim3(n_workgroups), dim3(256), 0, st, L); break;
+    case SK_KV_MFMA256:      SK_LAUNCH((sk_attn_bf16_d128<8, 1, 4>), dim3(n_workgroups), dim3(512)); break;
+    case SK_KV_MFMA128:      SK_LAUNCH((sk_attn_bf16_d128<4, 1, 2>), dim3(n_workgroups), dim3(256)); break;
+    case SK_KV_MFMA64:       SK_LAUNCH((sk_attn_bf16_d128<2, 2, 2>), dim3(n_workgroups), dim3(256)); break;
     default:
-        if (L.g.elem == 2) hipLaunchKernelGGL(sk_attn_simple<true>, dim3(n_workgroups), dim3(256), 0, st, L);
-        else hipLaunchKernelGGL(sk_attn_simple<false>, dim3(n_workgroups), dim3(256), 0, st, L);
+        if (L.g.elem == 2) SK_LAUNCH(sk_attn_simple<true>, dim3(n_workgroups), dim3(256));
+        else SK_LAUNCH(sk_attn_simple<false>, dim3(n_workgroups), dim3(256));
     }
     return (int)hipGetLastError();
 }
 
-int sk_launch_combine(const sk_launch& L, int32_t n_row_tiles, void* stream)
+int sk_launch_combine(const sk_launch& L, int32_t n_row_tiles, void* stream, void* ev_start, void* ev_stop)
 {
     if (n_row_tiles <= 0) return 0;
-    hipLaunchKernelGGL(sk_combine, dim3(n_row_tiles * (L.rows_per_slot >> 2)), dim3(256), 0, (hipStream_t)stream, L);
+    hipStream_t st = (hipStream_t)stream;
+    SK_LAUNCH(sk_combine, dim3(n_row_tiles * (L.rows_per_slot >> 2)), dim3(256));
     return (int)hipGetLastError();
 }
+#undef SK_LAUNCH
 
 int sk_launch_gather(const sk_geom& g, int32_t tbl_off, int64_t first, int64_t count,
                      void* k_out, void* v_out, void* stream)

@@ -147,8 +147,10 @@ struct sk_pool {
     int inject_site = 0, inject_countdown = 0;
     // optional kernel timing
     bool profiling = false;
-    std::vector<hipEvent_t> prof_ev;     // triples: before attention, after attention, after combine
-    size_t prof_used = 0;                // events in use
+    struct ProfRec { hipEvent_t start, stop; int32_t call, kind; };   // one kernel dispatch; kind 0 attention, 1 combine
+    std::vector<ProfRec> prof;           // records (events are created once and reused)
+    size_t prof_used = 0;                // records in use
+    int32_t prof_calls = 0;              // calls since the last read
 };
 
 namespace {
@@ -217,19 +219,25 @@ int ring_upload(sk_pool* p, int slot, size_t bytes, hipStream_t st)
     return ring_copy(p, slot, p->device ? (unsigned char*)p->d.workspace + p->L.off_meta : nullptr, bytes, st);
 }
 
-// With profiling on, reserves three events for this call and records the first.
-hipEvent_t* prof_begin(sk_pool* p, hipStream_t st)
+// With profiling on: a call announces itself (prof_call) and asks for a pair of events per kernel
+// it launches (prof_pair); the launchers hand them to the runtime, which stamps them with the
+// dispatch's own start and end times.
+constexpr size_t kProfMax = 4 * 4096;
+int32_t prof_call(sk_pool* p) { return p->profiling ? p->prof_calls++ : -1; }
+bool prof_pair(sk_pool* p, int32_t call, int32_t kind, void** start, void** stop)
 {
-    if (!p->profiling || p->prof_used + 3 > 3 * 4096) return nullptr;
-    while (p->prof_ev.size() < p->prof_used + 3) {
-        hipEvent_t ev;
-        if (hipEventCreate(&ev) != hipSuccess) return nullptr;
-        p->prof_ev.push_back(ev);
+    *start = *stop = nullptr;
+    if (call < 0 || p->prof_used >= kProfMax) return false;
+    if (p->prof.size() <= p->prof_used) {
+        sk_pool::ProfRec r = {};
+        if (hipEventCreate(&r.start) != hipSuccess) return false;
+        if (hipEventCreate(&r.stop) != hipSuccess) { (void)hipEventDestroy(r.start); return false; }
+        p->prof.push_back(r);
     }
-    hipEvent_t* pe = &p->prof_ev[p->prof_used];
-    p->prof_used += 3;
-    (void)hipEventRecord(pe[0], st);
-    return pe;
+    sk_pool::ProfRec& r = p->prof[p->prof_used++];
+    r.call = call; r.kind = kind;
+    *start = r.start; *stop = r.stop;
+    return true;
 }
 
 // Which attention kernel takes a tile of `max_rows` query rows per KV head.
@@ -352,18 +360,19 @@ int launch_regular(sk_pool* p, RegPlan& R, const void* q, void* out, int out_dty
         S.g = L.g; S.q = L.q; S.out = L.out; S.lse = L.lse; S.part_ml = L.part_ml; S.part_o = L.part_o; S.sync = L.sync;
         S.out_dtype = L.out_dtype;
     }
-    hipEvent_t* pe = prof_begin(p, st);
-    int e = sk_launch_attention(R.L, R.v.id, R.wgs, st);
+    const int32_t pc = prof_call(p);
+    void *e0, *e1;
+    prof_pair(p, pc, 0, &e0, &e1);
+    int e = sk_launch_attention(R.L, R.v.id, R.wgs, st, e0, e1);
     if (e) { g_last_hip = e; return SK_E_HIP; }
     p->stats.launches++;
-    if (pe) (void)hipEventRecord(pe[1], st);
     if (R.parts > 1 && !R.L.fuse) {
         // the attention kernel is enqueued and will write its partials; a failure here leaves out/lse unwritten
-        e = inject(p, SK_SITE_COMBINE) ? (int)hipErrorUnknown : sk_launch_combine(R.L, R.base_wgs, st);
+        prof_pair(p, pc, 1, &e0, &e1);
+        e = inject(p, SK_SITE_COMBINE) ? (int)hipErrorUnknown : sk_launch_combine(R.L, R.base_wgs, st, e0, e1);
         if (e) { g_last_hip = e; return SK_E_HIP; }
         p->stats.launches++;
     }
-    if (pe) (void)hipEventRecord(pe[2], st);
     p->stats.kv_bytes_streamed += R.kv_len * 2 * p->d.n_kv_heads * p->d.head_dim * p->L.elem * R.L.n_tiles;
     p->last.workgroups = R.wgs; p->last.n_splits = R.parts; p->last.row_tiles = R.L.n_tiles; p->last.kernel_variant = R.v.id;
     p->last.fused_merge = R.L.fuse;
@@ -740,7 +749,8 @@ int launch_list(sk_pool* p, ListPlan& P, const ScatterBatch* sb, int n_sb, ListG
     }
     if (inject(p, SK_SITE_ATTENTION)) return SK_E_HIP;
     if (!p->device) return SK_OK;
-    hipEvent_t* pe = prof_begin(p, st);
+    const int32_t pc = prof_call(p);
+    void *e0, *e1;
     sk_launch L[kMaxGroups];
     int32_t wgs = 0, max_parts = 1;
     for (int gi = 0; gi < n_groups; ++gi) {
@@ -755,20 +765,20 @@ int launch_list(sk_pool* p, ListPlan& P, const ScatterBatch* sb, int n_sb, ListG
         L[gi].fuse = P.fuse ? 1 : 0;
         L[gi].wait_polls = 0;          // the workgroups of a long list are not resident together
         L[gi].merge_fences = p->merge_fences ? 1 : 0;
-        int e = sk_launch_attention(L[gi], g.v.id, (int32_t)P.work[gi].size(), st);
+        prof_pair(p, pc, 0, &e0, &e1);
+        int e = sk_launch_attention(L[gi], g.v.id, (int32_t)P.work[gi].size(), st, e0, e1);
         if (e) { g_last_hip = e; return SK_E_HIP; }
         p->stats.launches++;
         wgs += (int32_t)P.work[gi].size();
         for (const sk_comb& c : P.comb[gi]) max_parts = std::max(max_parts, c.n_parts);
     }
-    if (pe) (void)hipEventRecord(pe[1], st);
     for (int gi = 0; gi < n_groups && !P.fuse; ++gi) {
         if (P.comb[gi].empty()) continue;
-        int e = sk_launch_combine(L[gi], (int32_t)P.comb[gi].size(), st);
+        prof_pair(p, pc, 1, &e0, &e1);
+        int e = sk_launch_combine(L[gi], (int32_t)P.comb[gi].size(), st, e0, e1);
         if (e) { g_last_hip = e; return SK_E_HIP; }
         p->stats.launches++;
     }
-    if (pe) (void)hipEventRecord(pe[2], st);
     p->stats.kv_bytes_streamed += P.kv_total * 2 * Hkv * p->d.head_dim * p->L.elem;
     p->last.workgroups = wgs; p->last.n_splits = max_parts; p->last.row_tiles = (int32_t)P.n_tiles;
     p->last.kernel_variant = groups[0].v.id;
@@ -871,7 +881,7 @@ int sk_pool_destroy(sk_pool* p)
     if (p->device) {
         for (int i = 0; i < kRingSlots; ++i)
             if (p->ring_ev[i]) (void)hipEventDestroy(p->ring_ev[i]);
-        for (hipEvent_t ev : p->prof_ev) (void)hipEventDestroy(ev);
+        for (sk_pool::ProfRec& r : p->prof) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
         if (p->ring) (void)hipHostFree(p->ring);
     }
     delete p;
@@ -1368,20 +1378,21 @@ int sk_pool_set_profiling(sk_pool* p, int enable)
 int sk_pool_read_profile(sk_pool* p, sk_profile* out, float* attn_pc, float* comb_pc, int32_t capacity)
 {
     if (!p || !out) return SK_E_INVAL;
-    out->calls = 0; out->attention_ms = 0; out->combine_ms = 0;
-    for (size_t i = 0; i + 3 <= p->prof_used; i += 3) {
-        float a = 0.f, c = 0.f;
-        SK_HIP(hipEventSynchronize(p->prof_ev[i + 2]));
-        SK_HIP(hipEventElapsedTime(&a, p->prof_ev[i], p->prof_ev[i + 1]));
-        SK_HIP(hipEventElapsedTime(&c, p->prof_ev[i + 1], p->prof_ev[i + 2]));
-        if (out->calls < capacity) {
-            if (attn_pc) attn_pc[out->calls] = a;
-            if (comb_pc) comb_pc[out->calls] = c;
-        }
-        out->calls++; out->attention_ms += a; out->combine_ms += c;
+    out->calls = p->prof_calls; out->attention_ms = 0; out->combine_ms = 0;
+    for (int32_t i = 0; i < p->prof_calls && i < capacity; ++i) {
+        if (attn_pc) attn_pc[i] = 0.f;
+        if (comb_pc) comb_pc[i] = 0.f;
     }
-    p->prof_used = 0;
-    return SK_OK;
+    int rc = SK_OK;
+    for (size_t i = 0; i < p->prof_used && rc == SK_OK; ++i) {
+        const sk_pool::ProfRec& r = p->prof[i];
+        float ms = 0.f;
+        if (hipEventSynchronize(r.stop) != hipSuccess || hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) { rc = SK_E_HIP; break; }
+        if (r.kind == 0) { out->attention_ms += ms; if (attn_pc && r.call < capacity) attn_pc[r.call] += ms; }
+        else { out->combine_ms += ms; if (comb_pc && r.call < capacity) comb_pc[r.call] += ms; }
+    }
+    p->prof_used = 0; p->prof_calls = 0;
+    return rc;
 }
 
 int64_t sk_pool_element_offset(const sk_pool* p, int64_t block, int32_t kv_head, int32_t is_v, int32_t slot, int32_t dim)
