@@ -115,6 +115,7 @@ size_t sk_pool_workspace_bytes(const sk_pool_desc* desc);
  *   SK_NO_PACK=1       a question batch gives every question a row tile of its own
  *   SK_NO_INTERLEAVE=1 the splits of a query take contiguous chunks of the cache instead of
  *                      interleaved 64-key pieces
+ *   SK_NO_P128=1       never the eight-wave (two key phases) instance of the 128-row tile
  *   SK_FUSE=1          single-session calls merge their split partials inside the attention kernel
  *                      instead of in a second kernel (one launch per call; measured slower on
  *                      MI355X, so not the default; the same function merges a row either way, the

@@ -90,8 +90,9 @@ struct sk_scatter {
 struct sk_scatter_list { sk_scatter item[SK_SCATTER_ARGS_MAX]; };
 
 enum { SK_MODE_REGULAR = 0, SK_MODE_LIST = 1 };
-// attention kernel variants: fp32-FMA kernel; bf16 MFMA kernel with 128-, 64- and 256-row tiles
-enum { SK_KV_SIMPLE = 0, SK_KV_MFMA128 = 1, SK_KV_MFMA64 = 2, SK_KV_MFMA256 = 3 };
+// attention kernel variants: fp32-FMA kernel; bf16 MFMA kernel with 128-, 64- and 256-row tiles; the
+// 128-row tile again with eight waves (two key phases per row group, one workgroup per CU)
+enum { SK_KV_SIMPLE = 0, SK_KV_MFMA128 = 1, SK_KV_MFMA64 = 2, SK_KV_MFMA256 = 3, SK_KV_MFMA128P = 4 };
 
 // Kernel argument block of the attention and combine kernels.
 struct sk_launch {

@@ -369,9 +369,14 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
     constexpr int NW = NRG * NPH;            // waves: 4 or 8
     constexpr int TPI = 2;                   // tiles per iteration (64 keys)
     constexpr int TPW = TPI / NPH;           // tiles per wave per iteration
-    static_assert(NW == 4 || (NW == 8 && NPH == 1 && NSS == 4), "four waves, or eight in two alternating groups");
+    // eight waves either as two groups of row groups that take turns (LOCKSTEP, 256 rows), or as two key
+    // phases per row group running freely (128 rows: half the arithmetic per wave of the four-wave
+    // 128-row instance, two waves per SIMD)
+    constexpr bool LOCKSTEP = NW == 8 && NPH == 1;
+    constexpr int NLG = NW / 4;              // groups of four waves; each loads whole tiles
+    static_assert(NW == 4 || (LOCKSTEP && NSS == 4) || (NW == 8 && NPH == 2 && NSS == 2), "four waves, or eight as described");
     static_assert(NSS == 2 || NSS == 4, "ring depth in iterations: 64 KiB (two workgroups per CU) or 128 KiB (one)");
-    static_assert(NSS * TPI >= NW, "the epilogue transposes one 16 KiB tile per wave in the ring");
+    static_assert(NSS * TPI >= (NPH == 1 ? NW : NRG), "the epilogue transposes one 16 KiB tile per wave (per row group with two phases) in the ring");
     // The ring holds NSS iterations of TPI tiles.  Its 1 KiB units are interleaved: unit u of tile t
     // of ring slot s sits at (u * TPI * NSS + t * NSS + s) KiB, so that from a lane's per-unit base
     // address every tile of the ring is within reach of the 16-bit offset field of an LDS read.
@@ -389,7 +394,8 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
     // Eight waves work as two groups of four that alternate between the matrix pipe and the vector
     // ALU (see the segment loop).  Waves i and i + 4 of a workgroup share a SIMD, so a SIMD holds
     // one wave of each group.  `sub` is the wave's index among the four that load a tile.
-    const int grp = NW == 8 ? (wave >> 2) : 0;
+    const int grp = LOCKSTEP ? (wave >> 2) : 0;
+    const int lg = NLG == 1 ? 0 : (wave >> 2);                     // which tiles of an iteration this wave helps to load (free-running path)
     const int sub = wave & 3;
     const unsigned unit_base = lds_base + sub * US;                // LDS address of this wave's unit of ring slot 0, tile 0
     const int r = lane & 31, kg = lane >> 5;
@@ -598,16 +604,18 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) asm volatile("" : : "v"(qreg[ks]));
 
-        if constexpr (NW == 4) {
-            // ---- four waves: every wave walks S, softmax, PV of an iteration in turn; overlap of
-            // matrix and vector work comes from the other workgroup on the CU ----
-            constexpr int LPW = 4 * TPI;         // direct-to-LDS loads per wave per iteration
+        if constexpr (!LOCKSTEP) {
+            // ---- free-running waves: every wave walks S, softmax, PV of an iteration in turn; overlap of
+            // matrix and vector work comes from the other wave of the SIMD (the other workgroup on the
+            // CU for the four-wave instances, the other key phase for the eight-wave one) ----
+            constexpr int LPW = 4 * TPI / NLG;   // direct-to-LDS loads per wave per iteration (tile p is loaded by wave group p % NLG)
             // prologue: iterations 0 .. NSS-2
 #pragma unroll
             for (int a = 0; a < NSS - 1; ++a) {
                 if (a < niter) {
 #pragma unroll
                     for (int p = 0; p < TPI; ++p) {
+                        if (NLG > 1 && (p % NLG) != lg) continue;
                         const int t0 = g.begin + a * g.step + p * SK_TILE;
                         const sk_tile_blocks tb = sk_lookup_tile(g, t0, last_group);
                         sk_issue_tile<US>(g, t0, last_group, tb, unit_base + SK_SLOT_OFF(a, p), koff, voff);
@@ -636,9 +644,11 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
                 sk_lds_barrier();
                 if (it + NSS - 1 < niter) {
 #pragma unroll
-                    for (int p = 0; p < TPI; ++p)
+                    for (int p = 0; p < TPI; ++p) {
+                        if (NLG > 1 && (p % NLG) != lg) continue;
                         sk_issue_tile<US>(g, g.begin + (it + NSS - 1) * g.step + p * SK_TILE, last_group, nb[p],
                                                        unit_base + SK_SLOT_OFF((slot + NSS - 1) % NSS, p), koff, voff);
+                    }
                     if (it + NSS < niter) {
 #pragma unroll
                         for (int p = 0; p < TPI; ++p)
@@ -812,33 +822,38 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
     float lx_tot; { const sk_halves h = sk_both_halves(lx_run); lx_tot = h.lo + h.hi; }
 
     if (NPH > 1) {
-        // merge the key phases of each row group through LDS: [value index][lane], value 64 = m, 65 = l, 66 = lx
+        // merge the key phases of each row group through LDS: [value index][lane], value 64 = m, 65 = l, 66 = lx;
+        // two row groups at a time (17 KiB each) so that four row groups fit the 64 KiB ring
         __syncthreads();
-        float* xch = (float*)&lds[0] + rg * (67 * 64);
-        if (ph == 1) {
+        float* xch = (float*)&lds[0] + (rg & 1) * (67 * 64);
+#pragma unroll 1
+        for (int round = 0; round < (NRG + 1) / 2; ++round) {
+            const bool mine = (rg >> 1) == round;
+            if (mine && ph == 1) {
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
+                for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) xch[(mt * 16 + v) * 64 + lane] = oacc[mt][v];
-            xch[64 * 64 + lane] = m_ref;
-            xch[65 * 64 + lane] = l_tot;
-            xch[66 * 64 + lane] = lx_tot;
+                    for (int v = 0; v < 16; ++v) xch[(mt * 16 + v) * 64 + lane] = oacc[mt][v];
+                xch[64 * 64 + lane] = m_ref;
+                xch[65 * 64 + lane] = l_tot;
+                xch[66 * 64 + lane] = lx_tot;
+            }
+            __syncthreads();
+            if (mine && ph == 0) {
+                const float m1 = xch[64 * 64 + lane], l1 = xch[65 * 64 + lane], lx1 = xch[66 * 64 + lane];
+                const float M = fmaxf(m_ref, m1);
+                const float a0 = (m_ref == SK_NEG_INF) ? 0.f : sk_exp2(m_ref - M);
+                const float a1 = (m1 == SK_NEG_INF) ? 0.f : sk_exp2(m1 - M);
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) oacc[mt][v] = oacc[mt][v] * a0 + xch[(mt * 16 + v) * 64 + lane] * a1;
+                l_tot = l_tot * a0 + l1 * a1;
+                lx_tot = lx_tot * a0 + lx1 * a1;
+                m_ref = M;
+            }
+            __syncthreads();                              // the exchange area is read; the next round and the transposes reuse it
         }
-        __syncthreads();
-        if (ph == 0) {
-        const float m1 = xch[64 * 64 + lane], l1 = xch[65 * 64 + lane], lx1 = xch[66 * 64 + lane];
-        const float M = fmaxf(m_ref, m1);
-        const float a0 = (m_ref == SK_NEG_INF) ? 0.f : sk_exp2(m_ref - M);
-        const float a1 = (m1 == SK_NEG_INF) ? 0.f : sk_exp2(m1 - M);
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) oacc[mt][v] = oacc[mt][v] * a0 + xch[(mt * 16 + v) * 64 + lane] * a1;
-        l_tot = l_tot * a0 + l1 * a1;
-        lx_tot = lx_tot * a0 + lx1 * a1;
-        m_ref = M;
-        }
-        __syncthreads();                                  // the exchange area is read; the transposes below reuse it
     }
 
     // ---- epilogue: rows go out through LDS so that every store instruction writes whole rows ----
@@ -850,7 +865,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
     const bool direct = w.part < 0;
     if (NPH == 1 || ph == 0) {                        // with two key phases, phase 0 holds the merged rows
         const float inv = direct ? 1.0f / l_tot : 1.0f;
-        float* tr = (float*)lds + (NPH == 1 ? wave : rg * 2) * 4096;
+        float* tr = (float*)lds + (NPH == 1 ? wave : rg) * 4096;
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
@@ -1270,6 +1285,7 @@ int sk_launch_attention(const sk_launch& L, int variant, int32_t n_workgroups, v
     case SK_KV_MFMA256:      SK_LAUNCH((sk_attn_bf16_d128<8, 1, 4>), dim3(n_workgroups), dim3(512)); break;
     case SK_KV_MFMA128:      SK_LAUNCH((sk_attn_bf16_d128<4, 1, 2>), dim3(n_workgroups), dim3(256)); break;
     case SK_KV_MFMA64:       SK_LAUNCH((sk_attn_bf16_d128<2, 2, 2>), dim3(n_workgroups), dim3(256)); break;
+    case SK_KV_MFMA128P:     SK_LAUNCH((sk_attn_bf16_d128<4, 2, 2>), dim3(n_workgroups), dim3(512)); break;
     default:
         if (L.g.elem == 2) SK_LAUNCH(sk_attn_simple<true>, dim3(n_workgroups), dim3(256));
         else SK_LAUNCH(sk_attn_simple<false>, dim3(n_workgroups), dim3(256));

@@ -138,6 +138,7 @@ struct sk_pool {
     int target_wgs = kDefaultTargetWgs;
     bool target_wgs_set = false;
     bool force_simple = false, no_256 = false, no_pack = false, no_interleave = false;
+    bool p128 = true;                    // SK_NO_P128=1: never the eight-wave 128-row instance
     bool fuse = false;                   // SK_FUSE=1: single-session calls merge their split partials inside the attention kernel
     bool fuse_list = false;              // batched calls too (the last workgroup of a unit merges alone)
     bool merge_fences = false;           // SK_MERGE_FENCES=1: full fences around the arrival (for comparison)
@@ -341,8 +342,12 @@ int plan_regular(const sk_pool* p, int32_t id, int64_t n_tok, int32_t pos0, int6
     // unit merges alone.  Not the default: a device-scope round trip (atomic, coherent load) measured about
     // 3 us on this hardware and the scheme needs four in a row, against 6-7 us for the combine kernel.
     const bool mfma = v.id != SK_KV_SIMPLE;
+    // A 128-row call that gives every CU at most one workgroup takes the eight-wave instance: two key
+    // phases per row group, so a wave has half the arithmetic per 64 keys and its SIMD a second wave
+    // to overlap it with.
+    if (p->p128 && v.id == SK_KV_MFMA128 && R.wgs <= p->n_cus) v.id = SK_KV_MFMA128P;
     L.fuse = (p->fuse && mfma && parts > 1 && base_wgs <= p->L.sync_units && parts < 65536) ? 1 : 0;
-    const int64_t resident = int64_t(p->n_cus) * (v.id == SK_KV_MFMA256 ? 1 : 2);
+    const int64_t resident = int64_t(p->n_cus) * ((v.id == SK_KV_MFMA256 || v.id == SK_KV_MFMA128P) ? 1 : 2);
     L.wait_polls = (L.fuse && R.wgs <= resident) ? p->wait_polls : 0;
     L.merge_fences = p->merge_fences ? 1 : 0;
     return SK_OK;
@@ -848,6 +853,7 @@ int sk_pool_create(const sk_pool_desc* desc, sk_pool** out)
     p->no_pack = env_on("SK_NO_PACK");
     p->no_interleave = env_on("SK_NO_INTERLEAVE");
     p->fuse = env_on("SK_FUSE");
+    p->p128 = !env_on("SK_NO_P128");
     p->fuse_list = env_on("SK_FUSE_LIST");
     p->merge_fences = env_on("SK_MERGE_FENCES");
     if (const char* t = getenv("SK_WAIT_POLLS")) { int x = atoi(t); if (x >= 0) p->wait_polls = x; }
