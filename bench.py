@@ -115,18 +115,20 @@ def measure_ceilings(sk):
     res = {}
     ramp(lambda i: sk.sk_probe_read(big, 2048, sink), 60.0, 4)
     best = None
-    for wgs in (1024, 2048, 4096, 8192):
-        us = stream_time_us(lambda i: sk.sk_probe_read(big, wgs, sink), 8)
-        best = us if best is None else min(best, us)
+    for nt in (False, True):
+        for wgs in (1024, 2048, 4096, 8192, 16384):
+            us = stream_time_us(lambda i: sk.sk_probe_read(big, wgs, sink, non_temporal=nt), 8)
+            best = us if best is None else min(best, us)
     res["stream_read_GBps"] = big.numel() / (best * 1e-6) / 1e9
     res["stream_read_frac_of_hbm_peak"] = res["stream_read_GBps"] / HBM_PEAK_GBPS
     # buffers of a query's size, rotating through the 2 GiB buffer so that every read is cold
     for name, nbytes in (("read_134MB_us", 32768 * 4096), ("read_537MB_us", 131072 * 4096)):
         n_off = big.numel() // nbytes
         best = None
-        for wgs in (256, 512, 1024, 2048, 4096):
-            t = stream_time_us(lambda i: sk.sk_probe_read(big[(i % n_off) * nbytes:], wgs, sink, nbytes=nbytes), 16)
-            best = t if best is None else min(best, t)
+        for nt in (False, True):
+            for wgs in (256, 512, 1024, 2048, 4096):
+                t = stream_time_us(lambda i: sk.sk_probe_read(big[(i % n_off) * nbytes:], wgs, sink, nbytes=nbytes, non_temporal=nt), 16)
+                best = t if best is None else min(best, t)
         res[name] = best
     del big
     fsink = torch.zeros(4, dtype=torch.float32, device="cuda")
@@ -141,8 +143,9 @@ def measure_ceilings(sk):
         us = stream_time_us(lambda i: sk.sk_probe_mfma(n_cus, 5000, fsink, ops), 20)
         res[key] = flops / (us * 1e-6) / 1e12
     res["mfma_bf16_frac_of_published_peak"] = res["mfma_bf16_TFLOPs"] / MFMA_BF16_PEAK_TFLOPS
-    res["how"] = ("sk_probe_read: 16-byte loads, eight in flight per thread, over a 2 GiB buffer (best of 1,024-8,192 workgroups) "
-                  "and over 134 / 537 MB pieces of it, never the same piece twice in a row (best of 256-4,096 workgroups), stream "
+    res["how"] = ("sk_probe_read: 16-byte loads, eight in flight per thread, default and non-temporal cache policy, over a 2 GiB buffer "
+                  "(best of 1,024-16,384 workgroups) and over 134 / 537 MB pieces of it, never the same piece twice in a row (best of "
+                  "256-4,096 workgroups), stream "
                   "timing; sk_probe_mfma: 8 waves per CU x 40,000 v_mfma_f32_32x32x16_bf16 on register operands drawn from N(0,1) "
                   "(or all ones), after 100 ms of the same load")
     return res

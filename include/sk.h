@@ -116,6 +116,8 @@ size_t sk_pool_workspace_bytes(const sk_pool_desc* desc);
  *   SK_NO_INTERLEAVE=1 the splits of a query take contiguous chunks of the cache instead of
  *                      interleaved 64-key pieces
  *   SK_NO_P128=1       never the eight-wave (two key phases) instance of the 128-row tile
+ *   SK_NO_STREAM_LOADS=1  calls with one row tile per KV head load the cache with the default cache
+ *                      policy instead of non-temporal
  *   SK_FUSE=1          single-session calls merge their split partials inside the attention kernel
  *                      instead of in a second kernel (one launch per call; measured slower on
  *                      MI355X, so not the default; the same function merges a row either way, the
@@ -327,8 +329,9 @@ int sk_pool_read_profile(sk_pool* pool, sk_profile* out, float* attention_ms_per
 /*
  * Measurement probes (benchmarks only; the attention path does not call them).
  * sk_probe_read: a plain streaming read of `bytes` bytes at src (DEVICE, 16-byte aligned) by
- * n_workgroups workgroups of 256 threads, 16 bytes per load; the time it takes is the floor of
- * anything that has to read that many bytes once (Sec. 3.2: a query reads the cache once).
+ * n_workgroups workgroups of 256 threads, 16 bytes per load (non_temporal != 0: with the cache
+ * policy for data used once); the time it takes is the floor of anything that has to read that
+ * many bytes once (Sec. 3.2: a query reads the cache once).
  * sk_probe_mfma: n_workgroups workgroups of eight waves, each wave `iters` rounds of eight bf16
  * 32x32x16 matrix products on register operands, read once from `operands` (DEVICE, bf16 data of
  * the caller's choice, operand_bytes >= 64, 16-byte aligned; the rate the pipe sustains depends on
@@ -336,7 +339,7 @@ int sk_pool_read_profile(sk_pool* pool, sk_profile* out, float* attention_ms_per
  * (HOST, optional) receives the floating-point operations of the launch.  sink: DEVICE, 4 bytes,
  * in practice never written.
  */
-int sk_probe_read(const void* src, size_t bytes, int32_t n_workgroups, void* sink, void* hip_stream);
+int sk_probe_read(const void* src, size_t bytes, int32_t n_workgroups, int32_t non_temporal, void* sink, void* hip_stream);
 int sk_probe_mfma(int32_t n_workgroups, int32_t iters, const void* operands, size_t operand_bytes, void* sink,
                   double* flops_out, void* hip_stream);
 

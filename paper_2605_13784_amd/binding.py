@@ -119,7 +119,7 @@ def lib():
     L.sk_top2.argtypes = [vp, i32, i32, i64, vp, ctypes.c_size_t, vp, vp, vp, vp, vp, vp]
     L.sk_top2_static.argtypes = [vp, i32, i32, i64, vp, vp, vp, vp, vp, vp]
     L.sk_pool_inject_failure.argtypes = [vp, i32, i32]
-    L.sk_probe_read.argtypes = [vp, ctypes.c_size_t, i32, vp, vp]
+    L.sk_probe_read.argtypes = [vp, ctypes.c_size_t, i32, i32, vp, vp]
     L.sk_probe_mfma.argtypes = [i32, i32, vp, ctypes.c_size_t, vp, P(ctypes.c_double), vp]
     L.sk_pool_set_profiling.argtypes = [vp, ctypes.c_int]
     L.sk_pool_read_profile.argtypes = [vp, P(sk_profile), P(ctypes.c_float), P(ctypes.c_float), i32]
@@ -403,10 +403,10 @@ def sk_top2(logits, stream=None, workspace=None, outputs=None):
     return idx1, idx2, val1, val2, gap
 
 
-def sk_probe_read(buf, n_workgroups, sink, stream=None, nbytes=None):
+def sk_probe_read(buf, n_workgroups, sink, stream=None, nbytes=None, non_temporal=False):
     """Plain streaming read of a CUDA tensor (measurement probe)."""
     nbytes = buf.numel() * buf.element_size() if nbytes is None else int(nbytes)
-    _ck(lib().sk_probe_read(_p(buf), nbytes, int(n_workgroups), _p(sink), _stream(stream)), "sk_probe_read")
+    _ck(lib().sk_probe_read(_p(buf), nbytes, int(n_workgroups), int(bool(non_temporal)), _p(sink), _stream(stream)), "sk_probe_read")
 
 
 def sk_probe_mfma(n_workgroups, iters, sink, operands=None, stream=None):

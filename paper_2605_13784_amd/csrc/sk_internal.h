@@ -128,7 +128,7 @@ struct sk_launch {
     int32_t fuse;
     int32_t wait_polls;
     int32_t merge_fences;   // 1: full device-scope fences around the arrival (slow: an L2 walk each); 0: see the kernel
-    int32_t pad2;
+    int32_t kv_once;        // 1: every key is read by exactly one workgroup of the launch (loaded non-temporal)
 };
 
 // Launchers implemented in sk_kernels.hip (return hipError_t as int).

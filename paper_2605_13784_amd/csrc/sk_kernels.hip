@@ -100,6 +100,7 @@ struct sk_seg {
     int32_t step;                // iteration i covers the 64 keys from begin + i * step (64: one contiguous run)
     int32_t pos_shift;           // absolute position = token index + pos_shift
     int32_t hole_lo, hole_n;     // tokens [hole_lo, hole_lo + hole_n) are evicted: streamed, never attended to
+    int32_t once;                // 1: no other workgroup of the launch reads these keys (load them non-temporal)
 };
 
 // Segment s of a work item: 0 = cached tokens, 1 = first uncommitted segment, 2 + k = second
@@ -114,6 +115,7 @@ __device__ __forceinline__ sk_seg sk_make_seg(const sk_launch& P, const sk_work&
         g.begin = w.kv_begin; g.end = w.kv_end; g.pos_shift = 0;
         g.step = w.kv_step > 0 ? w.kv_step : 64;
         g.hole_lo = w.hole_lo; g.hole_n = w.hole_hi - w.hole_lo;
+        g.once = P.kv_once;
     } else {
         g.base = P.g.eph + (int64_t)w.kv_head * P.g.eph_head_stride;
         g.table = P.g.eph_ident + (s == 1 ? w.eph_blk[0] : w.eph_blk[1] + (s - 2) * w.sub_blocks); g.blk_stride = P.g.eph_blk_stride;
@@ -121,6 +123,7 @@ __device__ __forceinline__ sk_seg sk_make_seg(const sk_launch& P, const sk_work&
         g.begin = 0; g.end = (s == 1 ? w.eph_cnt[0] : w.eph_cnt[1]); g.pos_shift = (s == 1 ? w.eph_pos0[0] : w.eph_pos0[1]);
         g.step = 64;
         g.hole_lo = 0; g.hole_n = 0;
+        g.once = 0;
     }
     return g;
 }
@@ -293,11 +296,17 @@ __device__ __forceinline__ void sk_lds_barrier()
 // One direct-to-LDS load of 16 bytes per lane: lane i's data lands at lds_addr + IMM + 16 i.
 // Written as inline assembly so that the compiler's automatic wait insertion does not drain the
 // tiles in flight before every LDS read; the waits are placed by hand (SK_WAIT_VMCNT).
-template <unsigned IMM>
+template <unsigned IMM, bool STREAM>
 __device__ __forceinline__ void sk_dma16(const void* base, unsigned lane_off, unsigned lds_addr)
 {   // address = base (scalar registers) + lane_off (one VGPR, unsigned)
-    asm volatile("s_add_u32 m0, %0, %3\n\tglobal_load_lds_dwordx4 %1, %2"
-                 : : "s"(lds_addr), "v"(lane_off), "s"(base), "n"(IMM) : "memory", "m0", "scc");
+    // STREAM marks the data as used once (cache policy "non-temporal"): it passes through the caches
+    // without displacing what other kernels left there.
+    if (STREAM)
+        asm volatile("s_add_u32 m0, %0, %3\n\tglobal_load_lds_dwordx4 %1, %2 nt"
+                     : : "s"(lds_addr), "v"(lane_off), "s"(base), "n"(IMM) : "memory", "m0", "scc");
+    else
+        asm volatile("s_add_u32 m0, %0, %3\n\tglobal_load_lds_dwordx4 %1, %2"
+                     : : "s"(lds_addr), "v"(lane_off), "s"(base), "n"(IMM) : "memory", "m0", "scc");
 }
 
 // 16-byte store that is written through to memory at once (cache policy "system coherent"), so that
@@ -352,8 +361,13 @@ __device__ __forceinline__ void sk_issue_group(const sk_seg& g, int t0, int last
         koff += slot0 << 8;          // K: 256 bytes per token
         voff += slot0 << 8;          // V^T: 4 KiB per 16-token group
     }
-    sk_dma16<J * 4 * US>(bb, koff, unit_addr);
-    sk_dma16<(8 + J * 4) * US>(bb, voff, unit_addr);
+    if (g.once) {       // uniform over the workgroup
+        sk_dma16<J * 4 * US, true>(bb, koff, unit_addr);
+        sk_dma16<(8 + J * 4) * US, true>(bb, voff, unit_addr);
+    } else {
+        sk_dma16<J * 4 * US, false>(bb, koff, unit_addr);
+        sk_dma16<(8 + J * 4) * US, false>(bb, voff, unit_addr);
+    }
 }
 template <unsigned US>
 __device__ __forceinline__ void sk_issue_tile(const sk_seg& g, int t0, int last_group, const sk_tile_blocks& tb,

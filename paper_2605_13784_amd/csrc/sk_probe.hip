@@ -13,20 +13,28 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 // Every thread reads 16-byte pieces `stride` apart and folds them into one word; the word is stored
 // only if it equals a value that the host picks at random, so the loads cannot be dropped and the
-// store practically never happens.
-__global__ __launch_bounds__(256) void sk_probe_read_kernel(const uint4* __restrict__ src, size_t n16, uint32_t never, uint32_t* sink)
+// store practically never happens.  NT: the loads carry the non-temporal cache policy.
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+template <bool NT>
+__device__ __forceinline__ uint32_t sk_probe_ld(const u32x4* p)
+{
+    const u32x4 a = NT ? __builtin_nontemporal_load(p) : *p;
+    return a.x ^ a.y ^ a.z ^ a.w;
+}
+template <bool NT>
+__global__ __launch_bounds__(256) void sk_probe_read_kernel(const u32x4* __restrict__ src, size_t n16, uint32_t never, uint32_t* sink)
 {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     uint32_t acc = 0;
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     for (; i + 7 * stride < n16; i += 8 * stride) {          // eight independent loads in flight per thread
-        uint4 x[8];
+        uint32_t x[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) x[u] = src[i + u * stride];
+        for (int u = 0; u < 8; ++u) x[u] = sk_probe_ld<NT>(src + i + u * stride);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) acc ^= x[u].x ^ x[u].y ^ x[u].z ^ x[u].w;
+        for (int u = 0; u < 8; ++u) acc ^= x[u];
     }
-    for (; i < n16; i += stride) { const uint4 a = src[i]; acc ^= a.x ^ a.y ^ a.z ^ a.w; }
+    for (; i < n16; i += stride) acc ^= sk_probe_ld<NT>(src + i);
     if (acc == never) sink[0] = acc;
 }
 
@@ -81,11 +89,15 @@ __global__ __launch_bounds__(512) void sk_probe_mfma_kernel(int iters, uint32_t 
 
 extern "C" {
 
-int sk_probe_read(const void* src, size_t bytes, int32_t n_workgroups, void* sink, void* hip_stream)
+int sk_probe_read(const void* src, size_t bytes, int32_t n_workgroups, int32_t non_temporal, void* sink, void* hip_stream)
 {
     if (!src || !sink || bytes < 16 || (uintptr_t)src % 16 || n_workgroups <= 0 || n_workgroups > (1 << 20)) return SK_E_INVAL;
-    hipLaunchKernelGGL(sk_probe_read_kernel, dim3((unsigned)n_workgroups), dim3(256), 0, (hipStream_t)hip_stream,
-                       (const uint4*)src, bytes / 16, 0x9e3779b9u, (uint32_t*)sink);
+    if (non_temporal)
+        hipLaunchKernelGGL(sk_probe_read_kernel<true>, dim3((unsigned)n_workgroups), dim3(256), 0, (hipStream_t)hip_stream,
+                           (const u32x4*)src, bytes / 16, 0x9e3779b9u, (uint32_t*)sink);
+    else
+        hipLaunchKernelGGL(sk_probe_read_kernel<false>, dim3((unsigned)n_workgroups), dim3(256), 0, (hipStream_t)hip_stream,
+                           (const u32x4*)src, bytes / 16, 0x9e3779b9u, (uint32_t*)sink);
     return hipGetLastError() == hipSuccess ? SK_OK : SK_E_HIP;
 }
 

@@ -101,6 +101,17 @@ def test_single_session_full_context(n, L, nq, n_rows, B):
         out, lse = pool.sk_session_query(sid, dev(qq), n_splits=S)
         ro, rl = ref.query(synth.to_raw(qq), rows=rows[:8])
         _check_rows("query A S=%d" % S, out, lse, rows[:8], ro, rl, shape.dtype)
+    if n > 65536 and B == 16:
+        # 32 tokens (128 rows per KV head) at this length: the eight-wave 128-row instance, which from
+        # 65,536 cached tokens on loads the cache with the non-temporal policy
+        q2, k2, v2 = synth.draw_qkv(gen, 32, shape)
+        rows2 = _sample_rows(rng, 32, shape, extra=4)[:12]
+        out, lse = pool.sk_session_query(sid, dev(q2))
+        ro, rl = ref.query(synth.to_raw(q2), rows=rows2)
+        _check_rows("32-token query A at %d" % n, out, lse, rows2, ro, rl, shape.dtype)
+        out, lse = pool.sk_session_query(sid, dev(q2), dev(k2), dev(v2))
+        ro, rl = ref.query(synth.to_raw(q2), synth.to_raw(k2), synth.to_raw(v2), rows=rows2)
+        _check_rows("32-token query B at %d" % n, out, lse, rows2, ro, rl, shape.dtype)
 
 
 def test_registered_question_batch_at_65536():
