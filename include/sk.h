@@ -116,8 +116,12 @@ size_t sk_pool_workspace_bytes(const sk_pool_desc* desc);
  *   SK_NO_INTERLEAVE=1 the splits of a query take contiguous chunks of the cache instead of
  *                      interleaved 64-key pieces
  *   SK_NO_P128=1       never the eight-wave (two key phases) instance of the 128-row tile
+ *   SK_P128_MIN_TOKENS=n  cached tokens from which a single-session call of 65-128 rows takes that
+ *                      instance (default 32768: below, its longer start outweighs the gain)
  *   SK_NO_STREAM_LOADS=1  calls with one row tile per KV head load the cache with the default cache
  *                      policy instead of non-temporal
+ *   SK_STREAM_MIN_TOKENS=n  cached tokens from which the 128-row instances do so (default 65536;
+ *                      the 64-row instance always does)
  *   SK_FUSE=1          single-session calls merge their split partials inside the attention kernel
  *                      instead of in a second kernel (one launch per call; measured slower on
  *                      MI355X, so not the default; the same function merges a row either way, the

@@ -139,6 +139,8 @@ struct sk_pool {
     bool target_wgs_set = false;
     bool force_simple = false, no_256 = false, no_pack = false, no_interleave = false, no_stream_loads = false;
     bool p128 = true;                    // SK_NO_P128=1: never the eight-wave 128-row instance
+    int64_t p128_min_tokens = 32768;     // SK_P128_MIN_TOKENS: cached tokens from which it is taken
+    int64_t stream_min_tokens = 65536;   // SK_STREAM_MIN_TOKENS: cached tokens from which the 128-row instances load non-temporal
     bool fuse = false;                   // SK_FUSE=1: single-session calls merge their split partials inside the attention kernel
     bool fuse_list = false;              // batched calls too (the last workgroup of a unit merges alone)
     bool merge_fences = false;           // SK_MERGE_FENCES=1: full fences around the arrival (for comparison)
@@ -344,8 +346,11 @@ int plan_regular(const sk_pool* p, int32_t id, int64_t n_tok, int32_t pos0, int6
     const bool mfma = v.id != SK_KV_SIMPLE;
     // A 128-row call that gives every CU at most one workgroup takes the eight-wave instance: two key
     // phases per row group, so a wave has half the arithmetic per 64 keys and its SIMD a second wave
-    // to overlap it with.
-    if (p->p128 && v.id == SK_KV_MFMA128 && R.wgs <= p->n_cus) v.id = SK_KV_MFMA128P;
+    // to overlap it with.  Measured (32-token query, us per query, four waves -> eight): 2,600 cached
+    // tokens 18.5 -> 20.1, 8K 22.8 -> 24.7, 14,800 28.3 -> 29.4, 32K 42.3 -> 42.1, 64K 69.5 -> 65.3,
+    // 128K 123.8 -> 113.2: the eight waves pay off once the stream outweighs their longer start and
+    // their merge of the two phases.
+    if (p->p128 && v.id == SK_KV_MFMA128 && R.wgs <= p->n_cus && kv_len >= p->p128_min_tokens) v.id = SK_KV_MFMA128P;
     L.fuse = (p->fuse && mfma && parts > 1 && base_wgs <= p->L.sync_units && parts < 65536) ? 1 : 0;
     const int64_t resident = int64_t(p->n_cus) * ((v.id == SK_KV_MFMA256 || v.id == SK_KV_MFMA128P) ? 1 : 2);
     L.wait_polls = (L.fuse && R.wgs <= resident) ? p->wait_polls : 0;
@@ -358,7 +363,7 @@ int plan_regular(const sk_pool* p, int32_t id, int64_t n_tok, int32_t pos0, int6
     //   129 - 256          37.8 -> 41.4   53.6 -> 56.8   90.7 -> 90.7   162.1 -> 162.0
     // so the 64-row instance always does, the 128-row instances from 64K cached tokens on, the 256-row
     // instance (and every call whose row tiles share their keys through the L2) never.
-    const bool once_pays = v.id == SK_KV_MFMA64 || ((v.id == SK_KV_MFMA128 || v.id == SK_KV_MFMA128P) && kv_len >= 65536);
+    const bool once_pays = v.id == SK_KV_MFMA64 || ((v.id == SK_KV_MFMA128 || v.id == SK_KV_MFMA128P) && kv_len >= p->stream_min_tokens);
     L.kv_once = (!p->no_stream_loads && L.n_tiles == 1 && once_pays) ? 1 : 0;
     return SK_OK;
 }
@@ -865,6 +870,8 @@ int sk_pool_create(const sk_pool_desc* desc, sk_pool** out)
     p->no_stream_loads = env_on("SK_NO_STREAM_LOADS");
     p->fuse = env_on("SK_FUSE");
     p->p128 = !env_on("SK_NO_P128");
+    if (const char* t = getenv("SK_P128_MIN_TOKENS")) { long long x = atoll(t); if (x >= 0) p->p128_min_tokens = x; }
+    if (const char* t = getenv("SK_STREAM_MIN_TOKENS")) { long long x = atoll(t); if (x >= 0) p->stream_min_tokens = x; }
     p->fuse_list = env_on("SK_FUSE_LIST");
     p->merge_fences = env_on("SK_MERGE_FENCES");
     if (const char* t = getenv("SK_WAIT_POLLS")) { int x = atoi(t); if (x >= 0) p->wait_polls = x; }

@@ -15,6 +15,7 @@ that the row is an exact convex combination of values, and takes the lse from th
 unrounded weights, kept beside it in fp32: what is left in the lse is the hardware exp2/log2 (about
 1 ulp each) and the fp32 summation, a few 1e-6 relative to a sum, far inside 1e-3.
 """
+import os
 import numpy as np
 import torch
 
@@ -59,11 +60,21 @@ class Pair:
     """One GPU pool and, per session, one oracle session fed identically."""
 
     def __init__(self, shape: synth.Shape, block_tokens=16, n_blocks=256, max_sessions=4, max_batch_tokens=0,
-                 alloc_perm=None, kv_fill=None, softmax_scale=0.0):
+                 alloc_perm=None, kv_fill=None, softmax_scale=0.0, env=None):
         self.shape = shape
-        self.pool = sk.Pool(shape.dtype, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, block_tokens, n_blocks,
-                            max_sessions=max_sessions, max_batch_tokens=max_batch_tokens, kv_fill=kv_fill,
-                            softmax_scale=softmax_scale)
+        # the library reads its tuning switches from the environment when a pool is created
+        old = {k: os.environ.get(k) for k in (env or {})}
+        os.environ.update(env or {})
+        try:
+            self.pool = sk.Pool(shape.dtype, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, block_tokens, n_blocks,
+                                max_sessions=max_sessions, max_batch_tokens=max_batch_tokens, kv_fill=kv_fill,
+                                softmax_scale=softmax_scale)
+        finally:
+            for k, x in old.items():
+                if x is None:
+                    os.environ.pop(k, None)
+                else:
+                    os.environ[k] = x
         if alloc_perm is not None:
             self.pool.sk_pool_set_alloc_order(alloc_perm)
         self.oracles = {}

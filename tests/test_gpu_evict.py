@@ -19,13 +19,15 @@ pytestmark = pytest.mark.gpu
     (synth.CFG2, 64, 37),         # blocks of 64: the hole spans whole key tiles of the kernel
     (synth.CFG2, 256, 0),         # no frozen region, large blocks: a hole of up to 255 tokens in front
     (synth.CFG1, 16, 21),         # fp32 kernel
+    (synth.CFG2, 16, 101),        # with the instance and the cache policy otherwise kept for long caches (below)
 ])
 def test_sliding_window_stream(shape, block_tokens, n_frozen):
     """A stream that keeps a window: append, evict what exceeds the capacity, query; several rounds,
     with eviction amounts that leave the hole at every alignment."""
     gen = synth.generator(2, stream=30 + block_tokens + n_frozen)
     cap = 900
-    pr = Pair(shape, block_tokens=block_tokens, n_blocks=4096 // block_tokens + 8, kv_fill=0xFF, max_batch_tokens=1024)
+    env = {"SK_P128_MIN_TOKENS": "0", "SK_STREAM_MIN_TOKENS": "0"} if n_frozen == 101 else None
+    pr = Pair(shape, block_tokens=block_tokens, n_blocks=4096 // block_tokens + 8, kv_fill=0xFF, max_batch_tokens=1024, env=env)
     sid = pr.create()
     if n_frozen:
         q, k, v = synth.draw_qkv(gen, n_frozen, shape)

@@ -32,14 +32,20 @@ def test_cfg1_fp32_single_session_every_step():
     assert pr.pool.sk_session_length(sid) == 1024
 
 
-@pytest.mark.parametrize("block_tokens", [16, 64])
-def test_bf16_gqa_ragged_appends_and_queries(block_tokens):
+# the instances and the cache policy that the library keeps for long caches, taken at any length
+LONG_CACHE_PATHS = {"SK_P128_MIN_TOKENS": "0", "SK_STREAM_MIN_TOKENS": "0"}
+
+
+@pytest.mark.parametrize("block_tokens,env", [(16, None), (64, None), (16, LONG_CACHE_PATHS)])
+def test_bf16_gqa_ragged_appends_and_queries(block_tokens, env):
     """Llama-3-8B-shaped layer (32/8 heads, d=128, bf16) at a size the oracle finishes in seconds:
     appends of ragged lengths (several row tiles, partial tiles, single tokens, block-straddling),
-    then queries of several lengths in both modes with several split counts."""
+    then queries of several lengths in both modes with several split counts; once more with the
+    eight-wave 128-row instance and the non-temporal loads that single-session calls of 65-128 rows
+    otherwise only take from 32,768 / 65,536 cached tokens on."""
     shape = synth.CFG2
     gen = synth.generator(2, stream=1)
-    pr = Pair(shape, block_tokens=block_tokens, n_blocks=4096 // block_tokens + 8, kv_fill=0xFF, max_batch_tokens=1024)
+    pr = Pair(shape, block_tokens=block_tokens, n_blocks=4096 // block_tokens + 8, kv_fill=0xFF, max_batch_tokens=1024, env=env)
     sid = pr.create()
     for i, L in enumerate([256, 100, 7, 1, 333, 64, 15, 1000]):
         q, k, v = synth.draw_qkv(gen, L, shape)
