@@ -240,5 +240,24 @@ def test_pool_of_160_gib_serves_a_session_from_its_last_blocks():
     torch.cuda.synchronize()
     Kc, Vc = ref.cache()
     assert np.array_equal(synth.to_raw(kc.cpu()), Kc) and np.array_equal(synth.to_raw(vc.cpu()), Vc)
+    # fork at a prefix that ends inside a block: the one block copy of a fork, here between two of the
+    # pool's highest blocks; then a cut of the source into a block it shares, whose next append copies
+    # that block first
+    fid = pool.sk_session_fork(sid, 700)
+    fref = ref.fork(700)
+    q, k, v = synth.draw_qkv(gen, 90, shape)
+    out, lse = pool.sk_session_append(fid, dev(q), dev(k), dev(v))
+    compare("append to the fork", out, lse, *fref.append(synth.to_raw(q), synth.to_raw(k), synth.to_raw(v)), shape.dtype)
+    pool.sk_session_truncate(sid, 650)
+    ref.truncate(650)
+    q, k, v = synth.draw_qkv(gen, 40, shape)
+    out, lse = pool.sk_session_append(sid, dev(q), dev(k), dev(v))
+    compare("append to the source after the cut", out, lse, *ref.append(synth.to_raw(q), synth.to_raw(k), synth.to_raw(v)), shape.dtype)
+    assert min(pool.sk_session_block_table(fid)) >= n_blocks - 256
+    for s_, r_ in ((sid, ref), (fid, fref)):
+        kc, vc = pool.sk_session_gather(s_)
+        torch.cuda.synchronize()
+        Kc, Vc = r_.cache()
+        assert np.array_equal(synth.to_raw(kc.cpu()), Kc) and np.array_equal(synth.to_raw(vc.cpu()), Vc)
     del pool
     torch.cuda.empty_cache()
