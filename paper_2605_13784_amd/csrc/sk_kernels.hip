@@ -396,7 +396,10 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
     // address every tile of the ring is within reach of the 16-bit offset field of an LDS read.
     constexpr unsigned US = TPI * NSS * 1024;                 // bytes from unit u to unit u + 1
 #define SK_SLOT_OFF(s, t) (((t) * NSS + (s)) * 1024)          // tile t of ring slot s, relative to unit bases
-    __shared__ __attribute__((aligned(16))) unsigned char lds[NSS * TPI * SK_TILE_BYTES];
+    // (with two key phases the merge of the phases needs 17 KiB per row group: 68 KiB for four row groups)
+    constexpr unsigned RING_BYTES = NSS * TPI * SK_TILE_BYTES;
+    constexpr unsigned XCH_BYTES = NPH > 1 ? NRG * 17 * 64 * 16 : 0;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[RING_BYTES > XCH_BYTES ? RING_BYTES : XCH_BYTES];
 
     sk_work w;
     if (!sk_decode_work(P, blockIdx.x, w)) return;
@@ -836,38 +839,40 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
     float lx_tot; { const sk_halves h = sk_both_halves(lx_run); lx_tot = h.lo + h.hi; }
 
     if (NPH > 1) {
-        // merge the key phases of each row group through LDS: [value index][lane], value 64 = m, 65 = l, 66 = lx;
-        // two row groups at a time (17 KiB each) so that four row groups fit the 64 KiB ring
-        __syncthreads();
-        float* xch = (float*)&lds[0] + (rg & 1) * (67 * 64);
-#pragma unroll 1
-        for (int round = 0; round < (NRG + 1) / 2; ++round) {
-            const bool mine = (rg >> 1) == round;
-            if (mine && ph == 1) {
+        // merge the key phases of each row group through LDS: per row group 17 x 64 float4 (lane-major, so a
+        // wave's 16-byte accesses are conflict-free): entries 0..15 the accumulators, entry 16 = (m, l, lx, -)
+        __syncthreads();                                  // every wave is done reading key tiles
+        float4* xch = (float4*)lds + rg * (17 * 64) + lane;
+        if (ph == 1) {
 #pragma unroll
-                for (int mt = 0; mt < 4; ++mt)
+            for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) xch[(mt * 16 + v) * 64 + lane] = oacc[mt][v];
-                xch[64 * 64 + lane] = m_ref;
-                xch[65 * 64 + lane] = l_tot;
-                xch[66 * 64 + lane] = lx_tot;
-            }
-            __syncthreads();
-            if (mine && ph == 0) {
-                const float m1 = xch[64 * 64 + lane], l1 = xch[65 * 64 + lane], lx1 = xch[66 * 64 + lane];
-                const float M = fmaxf(m_ref, m1);
-                const float a0 = (m_ref == SK_NEG_INF) ? 0.f : sk_exp2(m_ref - M);
-                const float a1 = (m1 == SK_NEG_INF) ? 0.f : sk_exp2(m1 - M);
-#pragma unroll
-                for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) oacc[mt][v] = oacc[mt][v] * a0 + xch[(mt * 16 + v) * 64 + lane] * a1;
-                l_tot = l_tot * a0 + l1 * a1;
-                lx_tot = lx_tot * a0 + lx1 * a1;
-                m_ref = M;
-            }
-            __syncthreads();                              // the exchange area is read; the next round and the transposes reuse it
+                for (int q4 = 0; q4 < 4; ++q4)
+                    xch[(mt * 4 + q4) * 64] = make_float4(oacc[mt][q4 * 4 + 0], oacc[mt][q4 * 4 + 1], oacc[mt][q4 * 4 + 2], oacc[mt][q4 * 4 + 3]);
+            xch[16 * 64] = make_float4(m_ref, l_tot, lx_tot, 0.f);
         }
+        __syncthreads();
+        if (ph == 0) {
+            const float4 s1 = xch[16 * 64];
+            const float m1 = s1.x, l1 = s1.y, lx1 = s1.z;
+            const float M = fmaxf(m_ref, m1);
+            const float a0 = (m_ref == SK_NEG_INF) ? 0.f : sk_exp2(m_ref - M);
+            const float a1 = (m1 == SK_NEG_INF) ? 0.f : sk_exp2(m1 - M);
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const float4 x = xch[(mt * 4 + q4) * 64];
+                    oacc[mt][q4 * 4 + 0] = oacc[mt][q4 * 4 + 0] * a0 + x.x * a1;
+                    oacc[mt][q4 * 4 + 1] = oacc[mt][q4 * 4 + 1] * a0 + x.y * a1;
+                    oacc[mt][q4 * 4 + 2] = oacc[mt][q4 * 4 + 2] * a0 + x.z * a1;
+                    oacc[mt][q4 * 4 + 3] = oacc[mt][q4 * 4 + 3] * a0 + x.w * a1;
+                }
+            l_tot = l_tot * a0 + l1 * a1;
+            lx_tot = lx_tot * a0 + lx1 * a1;
+            m_ref = M;
+        }
+        __syncthreads();                                  // the exchange area is read; the transposes reuse it
     }
 
     // ---- epilogue: rows go out through LDS so that every store instruction writes whole rows ----
