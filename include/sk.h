@@ -171,6 +171,10 @@ int sk_session_append(sk_pool* pool, int32_t id, const void* q, const void* k, c
  * sk_session_append would have written.  n_splits: partitions of the cached tokens
  * processed by separate workgroups and merged by log-sum-exp; 0 = chosen by the library.
  * An empty cache with k == NULL gives SK_E_EMPTY.  nq == 0 is a no-op.
+ * The call enqueues kernels only (its decomposition travels in the kernel arguments, and so does
+ * the list that stages its own k,v while they span at most 80 groups of 16 tokens): it can be
+ * captured in a HIP graph and replayed, as long as the session is not changed in between (its
+ * length is baked into the captured arguments).
  */
 int sk_session_query(sk_pool* pool, int32_t id, const void* q, const void* k, const void* v,
                      int32_t nq, void* out, int out_dtype, float* lse, int32_t n_splits,

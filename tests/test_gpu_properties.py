@@ -257,3 +257,58 @@ def test_merge_inside_the_kernel_equals_the_separate_combine_bit_for_bit():
     torch.cuda.synchronize()
     for p in pools:
         p.close()
+
+
+def test_query_replays_from_a_hip_graph():
+    """A single-session query enqueues kernels only (its decomposition and its short scatter list
+    travel in the kernel arguments), so a caller can capture it in a HIP graph and replay it: every
+    replay, with new query contents in the captured buffers and eager calls and synchronisations
+    in between, equals the eager call on the same inputs bit for bit, and the oracle within
+    tolerance.  The greedy sampler's entry point that allocates nothing is captured along."""
+    gen = synth.generator(2, stream=91)
+    pr = Pair(SHAPE, block_tokens=16, n_blocks=300, kv_fill=0xFF, max_batch_tokens=2048)
+    sid = pr.create()
+    q, k, v = synth.draw_qkv(gen, 1500, SHAPE)
+    pr.append(sid, q, k, v, check=False)
+    nq, vocab = 20, 8192 * 3 + 4
+    qs = torch.zeros((nq, SHAPE.n_q_heads, SHAPE.head_dim), dtype=torch.bfloat16, device="cuda")
+    ks = torch.zeros((nq, SHAPE.n_kv_heads, SHAPE.head_dim), dtype=torch.bfloat16, device="cuda")
+    vs = torch.zeros_like(ks)
+    logits = torch.zeros((nq, vocab), dtype=torch.float32, device="cuda")
+    out_a = torch.empty((nq, SHAPE.n_q_heads, SHAPE.head_dim), dtype=torch.float32, device="cuda")
+    lse_a = torch.empty((nq, SHAPE.n_q_heads), dtype=torch.float32, device="cuda")
+    out_b, lse_b = torch.empty_like(out_a), torch.empty_like(lse_a)
+    tops = sk.top2_outputs(nq, "cuda")
+    sk.sk_top2_static(logits[:0])                         # set-up call (no rows): resolves the scratch address outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        pr.pool.sk_session_query(sid, qs, out=out_a, lse=lse_a)
+        pr.pool.sk_session_query(sid, qs, ks, vs, out=out_b, lse=lse_b)
+        sk.sk_top2_static(logits, outputs=tops)
+        graph.capture_end()
+    torch.cuda.synchronize()
+    before = pr.pool.kv_mem.clone()
+    for rep in range(4):
+        q1, k1, v1 = synth.draw_qkv(gen, nq, SHAPE)
+        lg = synth.draw(gen, (nq, vocab), "f32")
+        qs.copy_(dev(q1)); ks.copy_(dev(k1)); vs.copy_(dev(v1)); logits.copy_(dev(lg))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (out_a, lse_a, out_b, lse_b)] + [t.clone() for t in tops]
+        # eager work of the program's own between the replays, then the same calls eagerly
+        ea = pr.pool.sk_session_query(sid, qs)
+        eb = pr.pool.sk_session_query(sid, qs, ks, vs)
+        et = sk.sk_top2(logits)
+        torch.cuda.synchronize()
+        for x, y in zip(got, list(ea) + list(eb) + list(et)):
+            assert torch.equal(x, y), "replay %d differs from the eager call" % rep
+        o = pr.oracles[sid]
+        ro, rl = o.query(synth.to_raw(q1))
+        compare("graph replay %d, query A" % rep, got[0], got[1], ro, rl, SHAPE.dtype)
+        ro, rl = o.query(synth.to_raw(q1), synth.to_raw(k1), synth.to_raw(v1))
+        compare("graph replay %d, query B" % rep, got[2], got[3], ro, rl, SHAPE.dtype)
+    assert torch.equal(before, pr.pool.kv_mem)
