@@ -416,8 +416,8 @@ def stream_workload(sk, name, args, steps, warmup, ceilings, calibrate=False, sw
 
 
 def latency_vs_cached_tokens(sk, ceilings, nq=32):
-    """Latency of a 32-token query against the cached length (the paper's context range, 2,600 and 14,800
-    tokens, and the two workload lengths), cold (rotation over sessions that together hold > 1 GiB, at
+    """Latency of a 32-token (and of a 16-token) query against the cached length (the paper's context
+    range, 2,600 and 14,800 tokens, the two workload lengths and 65,536 between them), cold (rotation over sessions that together hold > 1 GiB, at
     most 128 of them) and hot (one session); the bytes a query streams and the rate."""
     shape = synth.CFG2
     B = 16
@@ -425,7 +425,8 @@ def latency_vs_cached_tokens(sk, ceilings, nq=32):
     out_q = torch.empty((nq, shape.n_q_heads, shape.head_dim), dtype=torch.float32, device="cuda")
     lse_q = torch.empty((nq, shape.n_q_heads), dtype=torch.float32, device="cuda")
     points = {}
-    for n in (2600, 14800, 32768, 131072):
+    q16, out16, lse16 = qq[:16], out_q[:16], lse_q[:16]
+    for n in (2600, 14800, 32768, 65536, 131072):
         n_sessions = min(128, rotation_sessions(n * shape.kv_bytes_per_token))
         pool = sk.Pool(shape.dtype, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, B, n_sessions * ((n + B - 1) // B + 1),
                        max_sessions=n_sessions, max_batch_tokens=1024)
@@ -442,6 +443,12 @@ def latency_vs_cached_tokens(sk, ceilings, nq=32):
                           "rotation_bytes": n_sessions * n * shape.kv_bytes_per_token, "bytes_per_query": qb,
                           "kv_GBps_cold": qb / (c * 1e-6) / 1e9, "hbm_frac_cold": qb / (c * 1e-6) / 1e9 / HBM_PEAK_GBPS,
                           "splits": info["n_splits"], "workgroups": info["workgroups"]}
+        # the same with 16 query tokens (64 rows per KV head: the 64-row instance, bound by the stream alone)
+        c16 = stream_time_us(lambda i: pool.sk_session_query(sids[i % n_sessions], q16, out=out16, lse=lse16), reps, warm=min(n_sessions, 16))
+        h16 = stream_time_us(lambda i: pool.sk_session_query(sids[0], q16, out=out16, lse=lse16), reps, warm=4)
+        qb16 = query_bytes(shape, n, 16, B)
+        points[str(n)]["16_tokens"] = {"cold_us": c16, "hot_us": h16, "kv_GBps_cold": qb16 / (c16 * 1e-6) / 1e9,
+                                       "hbm_frac_cold": qb16 / (c16 * 1e-6) / 1e9 / HBM_PEAK_GBPS}
         pool.close()
     ns = sorted(int(k) for k in points)
     x = np.array([points[str(k)]["bytes_per_query"] for k in ns], dtype=np.float64)
