@@ -315,7 +315,9 @@ int plan_regular(const sk_pool* p, int32_t id, int64_t n_tok, int32_t pos0, int6
         S = std::max<int64_t>(1, (target + base_wgs / 2) / base_wgs);
     }
     int64_t chunk = kv_len > 0 ? (kv_len + S - 1) / S : 64;
-    if (n_splits_req <= 0) chunk = std::max<int64_t>(chunk, 256);    // at least four key tiles per workgroup
+    // at least four 64-key iterations per workgroup of the matrix-pipe kernels; the fp32-FMA kernel
+    // (32-key tiles, far slower per key) takes shorter pieces so that small caches still spread over the chip
+    if (n_splits_req <= 0) chunk = std::max<int64_t>(chunk, v.id == SK_KV_SIMPLE ? 64 : 256);
     chunk = (chunk + 63) / 64 * 64;
     S = kv_len > 0 ? (kv_len + chunk - 1) / chunk : 0;
     int64_t parts = std::max<int64_t>(1, S + has_eph);
