@@ -32,7 +32,7 @@ struct sk_geom {
     int32_t v_off;                // byte offset of V inside (block, head)
     int32_t eph_v_off;
     int32_t B, log2B;             // pool block_tokens
-    int32_t Hq, Hkv, G, log2G;    // log2G = -1 when G is not a power of two
+    int32_t Hq, Hkv, G, log2G;    // log2G = -1 when G is not a power of two (informational: the kernels divide by G)
     int32_t d;
     int32_t elem;                 // bytes per element (2 or 4)
     float scale_log2e;            // softmax scale * log2(e)

@@ -416,15 +416,20 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
     const int sub = wave & 3;
     const unsigned unit_base = lds_base + sub * US;                // LDS address of this wave's unit of ring slot 0, tile 0
     const int r = lane & 31, kg = lane >> 5;
-    const int log2G = P.g.log2G, G = P.g.G;
+    // Row i of a tile is head i % G of token i / G (any group size up to 32; rows past the last
+    // whole token of a tile are idle).  Rows are below 256, so the division is a multiplication by
+    // ceil(2^16 / G) and a shift, exactly.
+    const int G = P.g.G;
+    const unsigned g_magic = (65536u + (unsigned)G - 1u) / (unsigned)G;
+    auto div_g = [&](const int row) __attribute__((always_inline)) { return (int)(((unsigned)row * g_magic) >> 16); };
     const int row_in_tile = rg * 32 + r;
-    const int tok_local = row_in_tile >> log2G;
-    const int hq = w.kv_head * G + (row_in_tile & (G - 1));
+    const int tok_local = div_g(row_in_tile);
+    const int hq = w.kv_head * G + (row_in_tile - tok_local * G);
     const bool row_valid = tok_local < w.n_tok;
-    const int tok_per_rg = 32 >> log2G;
-    // positions of the first and last valid token of this wave (wave-uniform)
-    const int wave_tok_first = rg * tok_per_rg;
-    int wave_tok_last = wave_tok_first + tok_per_rg - 1;
+    // positions of the first and last valid token of this wave (wave-uniform); with a group size that
+    // does not divide 32 a token's rows can lie in two waves
+    const int wave_tok_first = div_g(rg * 32);
+    int wave_tok_last = div_g(rg * 32 + 31);
     if (wave_tok_last > w.n_tok - 1) wave_tok_last = w.n_tok - 1;
     const bool wave_has_rows = wave_tok_first < w.n_tok;
     const bool causal = w.pos0 < SK_NO_CAUSAL;
@@ -907,10 +912,10 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
             const int row = ((it + blockIdx.x) & 15) * 2 + (lane >> 5);
             const float4 val = *(const float4*)(tr + row * 128 + ((c4 ^ row) & 31) * 4);
             const int rit = rg * 32 + row;                 // row inside the tile
-            const int tok2 = rit >> log2G;
+            const int tok2 = div_g(rit);
             if (tok2 >= w.n_tok) continue;
             if (direct) {
-                const size_t orow = ((size_t)(w.q_tok0 + tok2) * P.g.Hq + w.kv_head * G + (rit & (G - 1)));
+                const size_t orow = ((size_t)(w.q_tok0 + tok2) * P.g.Hq + w.kv_head * G + (rit - tok2 * G));
                 if (P.out_dtype == 0) *(float4*)((float*)P.out + orow * 128 + c4 * 4) = val;
                 else {
                     const uint32_t lo = f32_to_bf16_bits(val.x) | ((uint32_t)f32_to_bf16_bits(val.y) << 16);
@@ -976,7 +981,8 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
         for (int k = k_lo; k < k_hi; ++k) {
             const int row_end = (k + 1) * rps < nrows ? (k + 1) * rps : nrows;
             for (int row = k * rps + wave; row < row_end; row += NW) {
-                const size_t orow = (size_t)(w.q_tok0 + (row >> log2G)) * P.g.Hq + w.kv_head * G + (row & (G - 1));
+                const int tok3 = div_g(row);
+                const size_t orow = (size_t)(w.q_tok0 + tok3) * P.g.Hq + w.kv_head * G + (row - tok3 * G);
                 sk_merge_row<true, 16>(P, (size_t)w.part0 * P.rows_per_slot + row, (size_t)P.g.Hkv * P.rows_per_slot, w.n_parts, orow, lane);
             }
         }

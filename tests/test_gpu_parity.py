@@ -4,6 +4,7 @@ import numpy as np
 import pytest
 import torch
 
+import paper_2605_13784_amd as sk
 from workloads import synth
 from gpu_common import Pair, compare, dev
 
@@ -106,9 +107,9 @@ def test_bf16_output_dtype_bf16_and_no_lse():
                                    synth.Shape("bf16", 8, 8, 128), synth.Shape("bf16", 32, 2, 128),
                                    synth.Shape("bf16", 32, 1, 128)])
 def test_other_shapes(shape):
-    """head_dim 64 and a group size that is not a power of two go through the fp32-FMA kernel;
-    G = 32, 16, 8 and 1 go through the MFMA kernel (a wave's 32 rows are then one token's heads,
-    two tokens, four tokens, 32 tokens)."""
+    """head_dim 64 goes through the fp32-FMA kernel; G = 32, 16, 8, 3 and 1 go through the MFMA kernel
+    (a wave's 32 rows are then one token's heads, two tokens, four tokens, ten tokens and two thirds
+    of another, 32 tokens)."""
     gen = synth.generator(9, stream=shape.n_q_heads)
     pr = Pair(shape, n_blocks=64)
     sid = pr.create()
@@ -119,6 +120,58 @@ def test_other_shapes(shape):
     q, k, v = synth.draw_qkv(gen, 9, shape)
     pr.query(sid, q, name="query A")
     pr.query(sid, q, k, v, n_splits=2, name="query B")
+
+
+@pytest.mark.parametrize("hq,hkv", [(28, 4), (12, 4), (40, 8), (6, 1)])
+def test_group_sizes_that_are_not_powers_of_two(hq, hkv):
+    """G = 7, 3, 5 and 6 on the matrix-pipe kernels: a tile holds floor(rows / G) tokens, its last rows
+    idle, and a token's heads can lie in two waves.  Appends over several row tiles, queries that take
+    the 64-, 128- and 256-row instances in both modes and with several split counts, a sliding window,
+    a batched step and a question batch."""
+    shape = synth.Shape("bf16", hq, hkv, 128)
+    G = hq // hkv
+    gen = synth.generator(9, stream=100 + hq)
+    pr = Pair(shape, n_blocks=200, max_sessions=3, max_batch_tokens=1024, kv_fill=0xFF)
+    sid = pr.create()
+    for L in [300, 1, 37, 150]:
+        q, k, v = synth.draw_qkv(gen, L, shape)
+        pr.append(sid, q, k, v, name="append L=%d" % L)
+        assert pr.pool.sk_pool_last_launch()["kernel_variant"] != 0
+    pr.check_cache(sid)
+    for rows in (64, 128, 256, 300):
+        nq = rows // G
+        q, k, v = synth.draw_qkv(gen, nq, shape)
+        pr.query(sid, q, name="query A nq=%d" % nq)
+        assert pr.pool.sk_pool_last_launch()["kernel_variant"] != 0
+        for S in (1, 3):
+            pr.query(sid, q, k, v, n_splits=S, name="query B nq=%d S=%d" % (nq, S))
+    pr.freeze(sid, 33)
+    pr.evict(sid, 101)
+    q, k, v = synth.draw_qkv(gen, 21, shape)
+    pr.query(sid, q, name="query A behind a hole")
+    pr.append(sid, q, k, v, name="append behind a hole")
+    pr.check_cache(sid)
+    # batched step: an append on a second session and a query on the first
+    other = pr.create()
+    counts = [90, 17]
+    cu = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    q, k, v = synth.draw_qkv(gen, int(cu[-1]), shape)
+    out, lse = pr.pool.sk_batch_step([other, sid], [sk.SK_OP_APPEND, sk.SK_OP_QUERY_B], cu, dev(q), dev(k), dev(v))
+    qr, kr, vr = synth.to_raw(q), synth.to_raw(k), synth.to_raw(v)
+    ro0, rl0 = pr.oracles[other].append(qr[:90], kr[:90], vr[:90])
+    ro1, rl1 = pr.oracles[sid].query(qr[90:], kr[90:], vr[90:])
+    compare("batch step", out, lse, np.concatenate([ro0, ro1]), np.concatenate([rl0, rl1]), shape.dtype)
+    pr.check_cache(other)
+    # question batch
+    P_, NQ, Sfx = 16, 5, 8
+    qp, kp, vp = synth.draw_qkv(gen, P_, shape)
+    qs, ks, vs = [t.reshape(NQ, Sfx, t.shape[1], 128) for t in synth.draw_qkv(gen, NQ * Sfx, shape)]
+    op, lp, os_, ls = pr.pool.sk_session_query_shared_prefix(sid, dev(qp), dev(kp), dev(vp), dev(qs), dev(ks), dev(vs))
+    rop, rlp, ros, rls = pr.oracles[sid].query_shared_prefix(synth.to_raw(qp), synth.to_raw(kp), synth.to_raw(vp),
+                                                             synth.to_raw(qs), synth.to_raw(ks), synth.to_raw(vs))
+    compare("question batch, prefix", op, lp, rop, rlp, shape.dtype)
+    compare("question batch, suffixes", os_.reshape(NQ * Sfx, hq, 128), ls.reshape(NQ * Sfx, hq),
+            ros.reshape(NQ * Sfx, hq, 128), rls.reshape(NQ * Sfx, hq), shape.dtype)
 
 
 def test_large_logits_and_needle():
