@@ -349,37 +349,45 @@ __device__ __forceinline__ sk_tile_blocks sk_lookup_tile(const sk_seg& g, int t0
 // and the 16-key group's offset inside a block of more than 16 tokens is added to those.
 // In LDS the sixteen 1 KiB units of a tile (K units 0-7, V^T units 8-15) lie US bytes apart, with
 // the same unit of the other tiles of the ring in between; `unit_addr` is the address of unit `sub`.
-template <unsigned US, int J>
+// With head_dim 64 the tile keeps this LDS layout and fills half of it: a K row holds 128 bytes, so
+// the lanes of the upper eight chunk positions sit the K load out (`k_lane`: a direct-to-LDS load
+// moves the active lanes only), and V^T has 64 dims, so only the waves with sub < 2 load it (`v_wave`).
+template <unsigned US, int J, int D>
 __device__ __forceinline__ void sk_issue_group(const sk_seg& g, int t0, int last_group, uint32_t blk,
-                                               unsigned unit_addr, unsigned koff, unsigned voff)
+                                               unsigned unit_addr, unsigned koff, unsigned voff, bool k_lane, bool v_wave)
 {
+    constexpr int LOG2_TOK_BYTES = D == 128 ? 8 : 7;       // K bytes per token and head = V^T bytes per token
     int tg = t0 + 16 * J;
     tg = tg < last_group ? tg : last_group;
-    const unsigned char* bb = g.base + ((uint64_t)blk << (g.log2B + 9));
+    const unsigned char* bb = g.base + ((uint64_t)blk << (g.log2B + LOG2_TOK_BYTES + 1));
     if (g.B > 16) {
         const unsigned slot0 = (unsigned)tg & (unsigned)(g.B - 1);
-        koff += slot0 << 8;          // K: 256 bytes per token
-        voff += slot0 << 8;          // V^T: 4 KiB per 16-token group
+        koff += slot0 << LOG2_TOK_BYTES;          // K: 256 (128) bytes per token
+        voff += slot0 << LOG2_TOK_BYTES;          // V^T: 4 (2) KiB per 16-token group
     }
     if (g.once) {       // uniform over the workgroup
-        sk_dma16<J * 4 * US, true>(bb, koff, unit_addr);
-        sk_dma16<(8 + J * 4) * US, true>(bb, voff, unit_addr);
+        if (D == 128 || k_lane) sk_dma16<J * 4 * US, true>(bb, koff, unit_addr);
+        if (D == 128 || v_wave) sk_dma16<(8 + J * 4) * US, true>(bb, voff, unit_addr);
     } else {
-        sk_dma16<J * 4 * US, false>(bb, koff, unit_addr);
-        sk_dma16<(8 + J * 4) * US, false>(bb, voff, unit_addr);
+        if (D == 128 || k_lane) sk_dma16<J * 4 * US, false>(bb, koff, unit_addr);
+        if (D == 128 || v_wave) sk_dma16<(8 + J * 4) * US, false>(bb, voff, unit_addr);
     }
 }
-template <unsigned US>
+template <unsigned US, int D>
 __device__ __forceinline__ void sk_issue_tile(const sk_seg& g, int t0, int last_group, const sk_tile_blocks& tb,
-                                              unsigned unit_addr, unsigned koff, unsigned voff)
+                                              unsigned unit_addr, unsigned koff, unsigned voff, bool k_lane, bool v_wave)
 {
-    sk_issue_group<US, 0>(g, t0, last_group, tb.blk[0], unit_addr, koff, voff);
-    sk_issue_group<US, 1>(g, t0, last_group, tb.blk[1], unit_addr, koff, voff);
+    sk_issue_group<US, 0, D>(g, t0, last_group, tb.blk[0], unit_addr, koff, voff, k_lane, v_wave);
+    sk_issue_group<US, 1, D>(g, t0, last_group, tb.blk[1], unit_addr, koff, voff, k_lane, v_wave);
 }
 
-template <int NRG, int NPH, int NSS>
-__global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_attn_bf16_d128(const sk_launch P)
+template <int NRG, int NPH, int NSS, int D>
+__device__ __forceinline__ void sk_attn_bf16_body(const sk_launch P)
 {
+    static_assert(D == 128 || (D == 64 && NSS == 2 && !(NRG == 8 && NPH == 1)),
+                  "head_dim 128, or 64 on the free-running instances (whose waits are all for every load)");
+    constexpr int NKS = D / 16;              // 16-dim slices of the QK^T contraction
+    constexpr int NMT = D / 32;              // 32-dim blocks of the output
     constexpr int NW = NRG * NPH;            // waves: 4 or 8
     constexpr int TPI = 2;                   // tiles per iteration (64 keys)
     constexpr int TPW = TPI / NPH;           // tiles per wave per iteration
@@ -449,11 +457,14 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
     {
         uint4 z = make_uint4(0, 0, 0, 0);
         const uint4* qp = (const uint4*)((const unsigned char*)P.q +
-                          ((size_t)(w.q_tok0 + (row_valid ? tok_local : 0)) * P.g.Hq + hq) * 256);
+                          ((size_t)(w.q_tok0 + (row_valid ? tok_local : 0)) * P.g.Hq + hq) * (D * 2));
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            uint4 x = qp[ks * 2 + kg];                 // rows past the tile re-read row 0, then zeroed
-            if (!row_valid) x = z;
+            uint4 x = z;
+            if (ks < NKS) {
+                x = qp[ks * 2 + kg];                   // rows past the tile re-read row 0, then zeroed
+                if (!row_valid) x = z;
+            }
             qreg[ks] = __builtin_bit_cast(bf16x8, x);
         }
     }
@@ -475,7 +486,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
     sk_lds_cptr vptr[4];
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks)       // K row tau is row tau % 4 of unit tau / 4
-        kptr[ks] = (sk_lds_cptr)lds + SK_SLOT_OFF(0, ph * TPW) + (tau >> 2) * US + (tau & 3) * 256 + (((ks * 2 + kg) ^ (tau & 15)) << 4);
+        kptr[ks] = (sk_lds_cptr)lds + SK_SLOT_OFF(0, ph * TPW) + (tau >> 2) * US + (tau & 3) * 256 + (((ks * 2 + kg) ^ (tau & (D / 8 - 1))) << 4);
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
         const int dd = mt * 32 + r;
@@ -495,9 +506,14 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
         const int lim_row = p_row < seg_last_pos ? p_row : seg_last_pos;
 
         // lane-dependent parts of the DMA source addresses for this segment
-        const unsigned koff = (unsigned)((sub * 4 + (lane >> 4)) * 256 + (((lane & 15) ^ (sub * 4 + (lane >> 4))) << 4));
+        // (head_dim 64: a K row has eight 16-byte chunks, swizzled among themselves, and the lanes of the
+        // upper eight chunk positions load nothing; V^T has dims for the first two waves only)
+        const int krow = sub * 4 + (lane >> 4);
+        const unsigned koff = (unsigned)(krow * (D * 2) + (((lane & 15) ^ (krow & (D / 8 - 1))) << 4));
+        const bool k_lane = (lane & 15) < D / 8;
         const int vdd = sub * 32 + (lane >> 1);
         const unsigned voff = (unsigned)(g.v_off + vdd * 32 + ((((lane & 1) ^ ((vdd >> 3) & 1))) << 4));
+        const bool v_wave = sub < NMT;
 
         // ---- the three steps of one iteration (64 keys) for this wave; the ring slot is a
         // compile-time constant so that it folds into the offset field of the LDS instructions ----
@@ -519,28 +535,28 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
             for (int t = 0; t < TPW; ++t)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) sacc[t][v] = 0.f;
-            sk_u32x4 ka[TPW][8];
+            sk_u32x4 ka[TPW][NKS];
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
+            for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
                 for (int t = 0; t < TPW; ++t)
                     ka[t][ks] = *(sk_lds_u4ptr)(kptr[ks] + soff + SK_SLOT_OFF(0, t));
             __builtin_amdgcn_s_setprio(2);     // the wave feeding the matrix pipe goes first
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
+            for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
                 for (int t = 0; t < TPW; ++t)
                     sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[t][ks]), qreg[ks], sacc[t], 0, 0, 0);
             __builtin_amdgcn_s_setprio(0);
             // all LDS reads first, then the MFMAs back to back (two independent chains)
-            __builtin_amdgcn_sched_group_barrier(0x100, 8 * TPW, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 8 * TPW, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, NKS * TPW, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, NKS * TPW, 0);
         };
         auto load_v_tile = [&](const int t, const int soff) __attribute__((always_inline)) {
 #pragma unroll
             for (int q = 0; q < 2; ++q)
 #pragma unroll
-                for (int mt = 0; mt < 4; ++mt)
+                for (int mt = 0; mt < NMT; ++mt)
                     va[t][q][mt] = *(sk_lds_u4ptr)(vptr[mt] + soff + SK_SLOT_OFF(0, t) + q * 4 * US);
         };
         // mask (only tiles that cross a limit), row maximum, P = exp2(s * scale - m), row sums
@@ -616,7 +632,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
 #pragma unroll
             for (int q = 0; q < 2; ++q)
 #pragma unroll
-                for (int mt = 0; mt < 4; ++mt)
+                for (int mt = 0; mt < NMT; ++mt)
                     oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[t][q][mt]), pb[t][q], oacc[mt], 0, 0, 0);
         };
 
@@ -624,7 +640,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
         // The query operand must have arrived before the loop (a wait for it placed by the
         // compiler inside the loop would drain the ring on every iteration).
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) asm volatile("" : : "v"(qreg[ks]));
+        for (int ks = 0; ks < NKS; ++ks) asm volatile("" : : "v"(qreg[ks]));
 
         if constexpr (!LOCKSTEP) {
             // ---- free-running waves: every wave walks S, softmax, PV of an iteration in turn; overlap of
@@ -640,7 +656,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
                         if (NLG > 1 && (p % NLG) != lg) continue;
                         const int t0 = g.begin + a * g.step + p * SK_TILE;
                         const sk_tile_blocks tb = sk_lookup_tile(g, t0, last_group);
-                        sk_issue_tile<US>(g, t0, last_group, tb, unit_base + SK_SLOT_OFF(a, p), koff, voff);
+                        sk_issue_tile<US, D>(g, t0, last_group, tb, unit_base + SK_SLOT_OFF(a, p), koff, voff, k_lane, v_wave);
                     }
                 }
             }
@@ -668,8 +684,8 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
 #pragma unroll
                     for (int p = 0; p < TPI; ++p) {
                         if (NLG > 1 && (p % NLG) != lg) continue;
-                        sk_issue_tile<US>(g, g.begin + (it + NSS - 1) * g.step + p * SK_TILE, last_group, nb[p],
-                                                       unit_base + SK_SLOT_OFF((slot + NSS - 1) % NSS, p), koff, voff);
+                        sk_issue_tile<US, D>(g, g.begin + (it + NSS - 1) * g.step + p * SK_TILE, last_group, nb[p],
+                                                       unit_base + SK_SLOT_OFF((slot + NSS - 1) % NSS, p), koff, voff, k_lane, v_wave);
                     }
                     if (it + NSS < niter) {
 #pragma unroll
@@ -721,7 +737,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
                 if (a < ahead && a < niter) {
                     const int t0 = g.begin + a * g.step + my_tile * SK_TILE;
                     const sk_tile_blocks tb = sk_lookup_tile(g, t0, last_group);
-                    sk_issue_tile<US>(g, t0, last_group, tb, unit_base + SK_SLOT_OFF(a, my_tile), koff, voff);
+                    sk_issue_tile<US, D>(g, t0, last_group, tb, unit_base + SK_SLOT_OFF(a, my_tile), koff, voff, k_lane, v_wave);
                 }
             }
             sk_tile_blocks nb = sk_lookup_tile(g, g.begin + ahead * g.step + my_tile * SK_TILE, last_group);
@@ -737,8 +753,8 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
             auto refill = [&](const int j) __attribute__((always_inline)) {
                 const int i = j + ahead;
                 if (i < niter) {
-                    sk_issue_tile<US>(g, g.begin + i * g.step + my_tile * SK_TILE, last_group, nb,
-                                                   unit_base + SK_SLOT_OFF(i & 3, my_tile), koff, voff);
+                    sk_issue_tile<US, D>(g, g.begin + i * g.step + my_tile * SK_TILE, last_group, nb,
+                                                   unit_base + SK_SLOT_OFF(i & 3, my_tile), koff, voff, k_lane, v_wave);
                     if (i + 1 < niter) nb = sk_lookup_tile(g, g.begin + (i + 1) * g.step + my_tile * SK_TILE, last_group);
                 }
             };
@@ -850,7 +866,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
         float4* xch = (float4*)lds + rg * (17 * 64) + lane;
         if (ph == 1) {
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
+            for (int mt = 0; mt < NMT; ++mt)
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4)
                     xch[(mt * 4 + q4) * 64] = make_float4(oacc[mt][q4 * 4 + 0], oacc[mt][q4 * 4 + 1], oacc[mt][q4 * 4 + 2], oacc[mt][q4 * 4 + 3]);
@@ -864,7 +880,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
             const float a0 = (m_ref == SK_NEG_INF) ? 0.f : sk_exp2(m_ref - M);
             const float a1 = (m1 == SK_NEG_INF) ? 0.f : sk_exp2(m1 - M);
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
+            for (int mt = 0; mt < NMT; ++mt)
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4) {
                     const float4 x = xch[(mt * 4 + q4) * 64];
@@ -891,7 +907,7 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
         const float inv = direct ? 1.0f / l_tot : 1.0f;
         float* tr = (float*)lds + (NPH == 1 ? wave : rg) * 4096;
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
+        for (int mt = 0; mt < NMT; ++mt)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
                 const int c4 = mt * 8 + q4 * 2 + kg;
@@ -903,27 +919,29 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
             if (direct) { if (P.lse) P.lse[orow_lane] = (m_ref + sk_log2(lx_tot)) * SK_LN2; }
             else sk_store16_through(P.part_ml + ((size_t)w.part * P.rows_per_slot + row_in_tile) * 4, make_float4(m_ref, l_tot, lx_tot, 0.f));
         }
-        const int c4 = lane & 31;
+        // a row is D / 4 chunks of four floats: a store instruction writes two rows (four at head_dim 64)
+        constexpr int CPR = D / 4, RPI = 64 / CPR, NIT = 32 / RPI;
+        const int c4 = lane & (CPR - 1);
 #pragma unroll
-        for (int it = 0; it < 16; ++it) {
+        for (int it = 0; it < NIT; ++it) {
             // the row order is rotated by the workgroup index: workgroups that finish together (short
             // contexts) would otherwise all write the same offset of their partial slots, which lie a
             // power of two apart, at the same time, and crowd onto a few memory channels
-            const int row = ((it + blockIdx.x) & 15) * 2 + (lane >> 5);
+            const int row = ((it + blockIdx.x) & (NIT - 1)) * RPI + lane / CPR;
             const float4 val = *(const float4*)(tr + row * 128 + ((c4 ^ row) & 31) * 4);
             const int rit = rg * 32 + row;                 // row inside the tile
             const int tok2 = div_g(rit);
             if (tok2 >= w.n_tok) continue;
             if (direct) {
                 const size_t orow = ((size_t)(w.q_tok0 + tok2) * P.g.Hq + w.kv_head * G + (rit - tok2 * G));
-                if (P.out_dtype == 0) *(float4*)((float*)P.out + orow * 128 + c4 * 4) = val;
+                if (P.out_dtype == 0) *(float4*)((float*)P.out + orow * D + c4 * 4) = val;
                 else {
                     const uint32_t lo = f32_to_bf16_bits(val.x) | ((uint32_t)f32_to_bf16_bits(val.y) << 16);
                     const uint32_t hi = f32_to_bf16_bits(val.z) | ((uint32_t)f32_to_bf16_bits(val.w) << 16);
-                    *(uint2*)((uint16_t*)P.out + orow * 128 + c4 * 4) = make_uint2(lo, hi);
+                    *(uint2*)((uint16_t*)P.out + orow * D + c4 * 4) = make_uint2(lo, hi);
                 }
             } else {
-                sk_store16_through(P.part_o + ((size_t)w.part * P.rows_per_slot + rit) * 128 + c4 * 4, val);
+                sk_store16_through(P.part_o + ((size_t)w.part * P.rows_per_slot + rit) * D + c4 * 4, val);
             }
         }
     }
@@ -994,6 +1012,18 @@ __global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_att
             __hip_atomic_store(cnt + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
+}
+
+// The kernels proper: head_dim 128 (all four instances) and head_dim 64 (the free-running ones).
+template <int NRG, int NPH, int NSS>
+__global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_attn_bf16_d128(const sk_launch P)
+{
+    sk_attn_bf16_body<NRG, NPH, NSS, 128>(P);
+}
+template <int NRG, int NPH, int NSS>
+__global__ __launch_bounds__(64 * NRG * NPH, NRG * NPH == 8 ? 1 : 2) void sk_attn_bf16_d64(const sk_launch P)
+{
+    sk_attn_bf16_body<NRG, NPH, NSS, 64>(P);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1306,11 +1336,22 @@ int sk_launch_attention(const sk_launch& L, int variant, int32_t n_workgroups, v
 {
     if (n_workgroups <= 0) return 0;
     hipStream_t st = (hipStream_t)stream;
+    if (variant != SK_KV_SIMPLE && L.g.d != 128 && !(L.g.d == 64 && variant != SK_KV_MFMA256)) return (int)hipErrorInvalidValue;
+    const bool d64 = L.g.d == 64;
     switch (variant) {
     case SK_KV_MFMA256:      SK_LAUNCH((sk_attn_bf16_d128<8, 1, 4>), dim3(n_workgroups), dim3(512)); break;
-    case SK_KV_MFMA128:      SK_LAUNCH((sk_attn_bf16_d128<4, 1, 2>), dim3(n_workgroups), dim3(256)); break;
-    case SK_KV_MFMA64:       SK_LAUNCH((sk_attn_bf16_d128<2, 2, 2>), dim3(n_workgroups), dim3(256)); break;
-    case SK_KV_MFMA128P:     SK_LAUNCH((sk_attn_bf16_d128<4, 2, 2>), dim3(n_workgroups), dim3(512)); break;
+    case SK_KV_MFMA128:
+        if (d64) SK_LAUNCH((sk_attn_bf16_d64<4, 1, 2>), dim3(n_workgroups), dim3(256));
+        else SK_LAUNCH((sk_attn_bf16_d128<4, 1, 2>), dim3(n_workgroups), dim3(256));
+        break;
+    case SK_KV_MFMA64:
+        if (d64) SK_LAUNCH((sk_attn_bf16_d64<2, 2, 2>), dim3(n_workgroups), dim3(256));
+        else SK_LAUNCH((sk_attn_bf16_d128<2, 2, 2>), dim3(n_workgroups), dim3(256));
+        break;
+    case SK_KV_MFMA128P:
+        if (d64) SK_LAUNCH((sk_attn_bf16_d64<4, 2, 2>), dim3(n_workgroups), dim3(512));
+        else SK_LAUNCH((sk_attn_bf16_d128<4, 2, 2>), dim3(n_workgroups), dim3(512));
+        break;
     default:
         if (L.g.elem == 2) SK_LAUNCH(sk_attn_simple<true>, dim3(n_workgroups), dim3(256));
         else SK_LAUNCH(sk_attn_simple<false>, dim3(n_workgroups), dim3(256));

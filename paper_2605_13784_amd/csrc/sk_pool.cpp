@@ -251,9 +251,10 @@ struct Variant { int id; int rows_per_slot; int tok_per_tile; };
 bool pick_variant(const sk_pool* p, int64_t n_tok, Variant& v, bool allow_256 = false)
 {
     const int G = p->L.G;
-    const bool mfma_ok = p->d.dtype == SK_BF16 && p->d.head_dim == 128 && G <= 32;   // any group size: a tile holds floor(rows / G) tokens
+    // any group size: a tile holds floor(rows / G) tokens; head_dim 64 has no 256-row instance
+    const bool mfma_ok = p->d.dtype == SK_BF16 && (p->d.head_dim == 128 || p->d.head_dim == 64) && G <= 32;
     if (mfma_ok && !p->force_simple) {
-        if (allow_256 && n_tok * G > 128) { v.id = SK_KV_MFMA256; v.rows_per_slot = 256; v.tok_per_tile = 256 / G; }
+        if (allow_256 && p->d.head_dim == 128 && n_tok * G > 128) { v.id = SK_KV_MFMA256; v.rows_per_slot = 256; v.tok_per_tile = 256 / G; }
         else if (n_tok * G > 64) { v.id = SK_KV_MFMA128; v.rows_per_slot = 128; v.tok_per_tile = 128 / G; }
         else { v.id = SK_KV_MFMA64; v.rows_per_slot = 64; v.tok_per_tile = 64 / G; }
         return true;
@@ -1208,8 +1209,8 @@ int sk_session_query_shared_prefix(sk_pool* p, int32_t id, const void* qp, const
         // kernel (their rows see the same cache and prefix; each sees its own suffix), when a
         // question's rows are a multiple of a wave's 32 and divide 256.
         const int64_t rows_q = int64_t(Sfx) * p->L.G;
-        const bool pack = groups[1].v.id != SK_KV_SIMPLE && rows_q < 256 && rows_q % 32 == 0 && 256 % rows_q == 0 && NQ > 1 &&
-                          !p->no_pack;
+        const bool pack = groups[1].v.id != SK_KV_SIMPLE && p->d.head_dim == 128 && rows_q < 256 && rows_q % 32 == 0 &&
+                          256 % rows_q == 0 && NQ > 1 && !p->no_pack;
         const int32_t per_tile = pack ? int32_t(256 / rows_q) : 1;
         if (pack) groups[1].v = Variant{SK_KV_MFMA256, 256, 256 / p->L.G};
         for (int32_t j = 0; j < NQ; ++j)

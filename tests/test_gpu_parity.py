@@ -107,9 +107,9 @@ def test_bf16_output_dtype_bf16_and_no_lse():
                                    synth.Shape("bf16", 8, 8, 128), synth.Shape("bf16", 32, 2, 128),
                                    synth.Shape("bf16", 32, 1, 128)])
 def test_other_shapes(shape):
-    """head_dim 64 goes through the fp32-FMA kernel; G = 32, 16, 8, 3 and 1 go through the MFMA kernel
+    """fp32 goes through the fp32-FMA kernel; bf16 with G = 32, 16, 8, 3 and 1 through the MFMA kernel
     (a wave's 32 rows are then one token's heads, two tokens, four tokens, ten tokens and two thirds
-    of another, 32 tokens)."""
+    of another, 32 tokens), head_dim 64 included."""
     gen = synth.generator(9, stream=shape.n_q_heads)
     pr = Pair(shape, n_blocks=64)
     sid = pr.create()
@@ -122,13 +122,15 @@ def test_other_shapes(shape):
     pr.query(sid, q, k, v, n_splits=2, name="query B")
 
 
-@pytest.mark.parametrize("hq,hkv", [(28, 4), (12, 4), (40, 8), (6, 1)])
-def test_group_sizes_that_are_not_powers_of_two(hq, hkv):
+@pytest.mark.parametrize("hq,hkv,d", [(28, 4, 128), (12, 4, 128), (40, 8, 128), (6, 1, 128),
+                                      (32, 8, 64), (14, 2, 64), (8, 8, 64), (16, 1, 64)])
+def test_group_sizes_and_head_dim_64_on_the_matrix_pipe(hq, hkv, d):
     """G = 7, 3, 5 and 6 on the matrix-pipe kernels: a tile holds floor(rows / G) tokens, its last rows
-    idle, and a token's heads can lie in two waves.  Appends over several row tiles, queries that take
-    the 64-, 128- and 256-row instances in both modes and with several split counts, a sliding window,
-    a batched step and a question batch."""
-    shape = synth.Shape("bf16", hq, hkv, 128)
+    idle, and a token's heads can lie in two waves.  head_dim 64 (G = 4, 7, 1, 16) on the same kernels:
+    half of every K row and of the V^T dims of a tile.  Appends over several row tiles, queries that
+    take the 64-, 128- and 256-row instances in both modes and with several split counts, a sliding
+    window, a batched step and a question batch."""
+    shape = synth.Shape("bf16", hq, hkv, d)
     G = hq // hkv
     gen = synth.generator(9, stream=100 + hq)
     pr = Pair(shape, n_blocks=200, max_sessions=3, max_batch_tokens=1024, kv_fill=0xFF)
@@ -165,13 +167,13 @@ def test_group_sizes_that_are_not_powers_of_two(hq, hkv):
     # question batch
     P_, NQ, Sfx = 16, 5, 8
     qp, kp, vp = synth.draw_qkv(gen, P_, shape)
-    qs, ks, vs = [t.reshape(NQ, Sfx, t.shape[1], 128) for t in synth.draw_qkv(gen, NQ * Sfx, shape)]
+    qs, ks, vs = [t.reshape(NQ, Sfx, t.shape[1], d) for t in synth.draw_qkv(gen, NQ * Sfx, shape)]
     op, lp, os_, ls = pr.pool.sk_session_query_shared_prefix(sid, dev(qp), dev(kp), dev(vp), dev(qs), dev(ks), dev(vs))
     rop, rlp, ros, rls = pr.oracles[sid].query_shared_prefix(synth.to_raw(qp), synth.to_raw(kp), synth.to_raw(vp),
                                                              synth.to_raw(qs), synth.to_raw(ks), synth.to_raw(vs))
     compare("question batch, prefix", op, lp, rop, rlp, shape.dtype)
-    compare("question batch, suffixes", os_.reshape(NQ * Sfx, hq, 128), ls.reshape(NQ * Sfx, hq),
-            ros.reshape(NQ * Sfx, hq, 128), rls.reshape(NQ * Sfx, hq), shape.dtype)
+    compare("question batch, suffixes", os_.reshape(NQ * Sfx, hq, d), ls.reshape(NQ * Sfx, hq),
+            ros.reshape(NQ * Sfx, hq, d), rls.reshape(NQ * Sfx, hq), shape.dtype)
 
 
 def test_large_logits_and_needle():
