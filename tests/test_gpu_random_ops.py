@@ -270,6 +270,8 @@ class Walk:
     (synth.Shape("bf16", 12, 4, 128), 128, 3, 106, 200),
     (synth.Shape("bf16", 8, 1, 128), 16, 4, 107, 300),
     (synth.Shape("f32", 8, 2, 128), 32, 4, 108, 200),
+    (synth.Shape("bf16", 14, 2, 64), 16, 4, 109, 400),       # head_dim 64, seven query heads per KV head
+    (synth.Shape("bf16", 32, 8, 64), 64, 4, 110, 200),
 ])
 def test_random_walk_over_the_session_api(shape, block_tokens, max_sessions, seed, n_ops):
     Walk(shape, block_tokens, max_sessions, seed).run(n_ops)
