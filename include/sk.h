@@ -82,9 +82,9 @@ typedef struct sk_pool_desc {
                                  commit is a bit copy) */
     int32_t n_q_heads;        /* multiple of n_kv_heads */
     int32_t n_kv_heads;
-    int32_t head_dim;         /* 64 or 128.  bf16 pools with at most 32 query heads per KV head
-                                 (any such group size) run on the matrix pipe; fp32 pools and wider
-                                 groups take the fp32-FMA kernel (at most 16 per KV head) */
+    int32_t head_dim;         /* 64 or 128.  bf16 pools with at most 128 query heads per KV head
+                                 (any such group size) run on the matrix pipe; fp32 pools take the
+                                 fp32-FMA kernel (at most 16 per KV head) */
     int32_t block_tokens;     /* power of two, 16..1024 */
     int32_t max_sessions;     /* >= 1 */
     int64_t n_blocks;         /* blocks in the pool */

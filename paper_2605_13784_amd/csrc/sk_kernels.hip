@@ -424,7 +424,7 @@ __device__ __forceinline__ void sk_attn_bf16_body(const sk_launch P)
     const int sub = wave & 3;
     const unsigned unit_base = lds_base + sub * US;                // LDS address of this wave's unit of ring slot 0, tile 0
     const int r = lane & 31, kg = lane >> 5;
-    // Row i of a tile is head i % G of token i / G (any group size up to 32; rows past the last
+    // Row i of a tile is head i % G of token i / G (any group size up to 128; rows past the last
     // whole token of a tile are idle).  Rows are below 256, so the division is a multiplication by
     // ceil(2^16 / G) and a shift, exactly.
     const int G = P.g.G;

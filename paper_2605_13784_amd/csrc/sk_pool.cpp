@@ -251,11 +251,12 @@ struct Variant { int id; int rows_per_slot; int tok_per_tile; };
 bool pick_variant(const sk_pool* p, int64_t n_tok, Variant& v, bool allow_256 = false)
 {
     const int G = p->L.G;
-    // any group size: a tile holds floor(rows / G) tokens; head_dim 64 has no 256-row instance
-    const bool mfma_ok = p->d.dtype == SK_BF16 && (p->d.head_dim == 128 || p->d.head_dim == 64) && G <= 32;
+    // any group size up to 128 (multi-query models): a tile holds floor(rows / G) tokens, at least one;
+    // head_dim 64 has no 256-row instance
+    const bool mfma_ok = p->d.dtype == SK_BF16 && (p->d.head_dim == 128 || p->d.head_dim == 64) && G <= 128;
     if (mfma_ok && !p->force_simple) {
         if (allow_256 && p->d.head_dim == 128 && n_tok * G > 128) { v.id = SK_KV_MFMA256; v.rows_per_slot = 256; v.tok_per_tile = 256 / G; }
-        else if (n_tok * G > 64) { v.id = SK_KV_MFMA128; v.rows_per_slot = 128; v.tok_per_tile = 128 / G; }
+        else if (n_tok * G > 64 || G > 64) { v.id = SK_KV_MFMA128; v.rows_per_slot = 128; v.tok_per_tile = 128 / G; }
         else { v.id = SK_KV_MFMA64; v.rows_per_slot = 64; v.tok_per_tile = 64 / G; }
         return true;
     }

@@ -123,11 +123,13 @@ def test_other_shapes(shape):
 
 
 @pytest.mark.parametrize("hq,hkv,d", [(28, 4, 128), (12, 4, 128), (40, 8, 128), (6, 1, 128),
-                                      (32, 8, 64), (14, 2, 64), (8, 8, 64), (16, 1, 64)])
+                                      (32, 8, 64), (14, 2, 64), (8, 8, 64), (16, 1, 64),
+                                      (48, 1, 128), (71, 1, 64), (128, 1, 128)])
 def test_group_sizes_and_head_dim_64_on_the_matrix_pipe(hq, hkv, d):
     """G = 7, 3, 5 and 6 on the matrix-pipe kernels: a tile holds floor(rows / G) tokens, its last rows
     idle, and a token's heads can lie in two waves.  head_dim 64 (G = 4, 7, 1, 16) on the same kernels:
-    half of every K row and of the V^T dims of a tile.  Appends over several row tiles, queries that
+    half of every K row and of the V^T dims of a tile.  Multi-query shapes with 48, 71 and 128 heads on one
+    KV head: a token then fills most of a tile, or two waves and more.  Appends over several row tiles, queries that
     take the 64-, 128- and 256-row instances in both modes and with several split counts, a sliding
     window, a batched step and a question batch."""
     shape = synth.Shape("bf16", hq, hkv, d)
@@ -141,7 +143,7 @@ def test_group_sizes_and_head_dim_64_on_the_matrix_pipe(hq, hkv, d):
         assert pr.pool.sk_pool_last_launch()["kernel_variant"] != 0
     pr.check_cache(sid)
     for rows in (64, 128, 256, 300):
-        nq = rows // G
+        nq = max(1, rows // G)
         q, k, v = synth.draw_qkv(gen, nq, shape)
         pr.query(sid, q, name="query A nq=%d" % nq)
         assert pr.pool.sk_pool_last_launch()["kernel_variant"] != 0
