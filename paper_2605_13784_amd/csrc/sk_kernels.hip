@@ -233,12 +233,15 @@ __device__ __forceinline__ void sk_merge_row(const sk_launch& P, const size_t pr
 }
 
 // ---------------------------------------------------------------------------------------------
-// bf16 MFMA attention kernel, head_dim 128.
+// bf16 MFMA attention kernel, head_dim D = 128 (described below) or 64 (the same with four instead
+// of eight 16-dim slices of the first contraction and two instead of four 32-dim blocks of the
+// second, in the same LDS layout, half filled; the free-running instances only).
 //
 // Workgroup = NRG row groups x NPH key phases = 4 or 8 waves: a row group owns 32 query rows, a
 // phase owns every NPH-th key tile.  Instances: <4,1,2> 128-row tile; <2,2,2> 64-row tile, the two
-// phases merged through LDS at the end; <8,1,4> 256-row tile, eight waves in two groups that take
-// turns on the matrix pipe and the vector ALU (described at the segment loop).
+// phases merged through LDS at the end; <4,2,2> 128-row tile, eight waves as four row groups x two
+// phases; <8,1,4> 256-row tile, eight waves in two groups that take turns on the matrix pipe and
+// the vector ALU (described at the segment loop).
 //
 // Keys move HBM -> LDS with direct-to-LDS loads (global_load_lds_dwordx4), never through
 // registers, into a ring of NSS iterations of two 32-key tiles (K 8 KiB + V^T 8 KiB each): 64 KiB
