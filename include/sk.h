@@ -119,7 +119,7 @@ size_t sk_pool_workspace_bytes(const sk_pool_desc* desc);
  *                      interleaved 64-key pieces
  *   SK_NO_P128=1       never the eight-wave (two key phases) instance of the 128-row tile
  *   SK_P128_MIN_TOKENS=n  cached tokens from which a single-session call of 65-128 rows takes that
- *                      instance (default 32768: below, its longer start outweighs the gain)
+ *                      instance (default 30720: below, its longer start outweighs the gain)
  *   SK_NO_STREAM_LOADS=1  calls with one row tile per KV head load the cache with the default cache
  *                      policy instead of non-temporal
  *   SK_STREAM_MIN_TOKENS=n  cached tokens from which the 128-row instances do so (default 65536;

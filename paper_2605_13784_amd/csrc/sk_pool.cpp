@@ -139,7 +139,7 @@ struct sk_pool {
     bool target_wgs_set = false;
     bool force_simple = false, no_256 = false, no_pack = false, no_interleave = false, no_stream_loads = false;
     bool p128 = true;                    // SK_NO_P128=1: never the eight-wave 128-row instance
-    int64_t p128_min_tokens = 32768;     // SK_P128_MIN_TOKENS: cached tokens from which it is taken
+    int64_t p128_min_tokens = 30720;     // SK_P128_MIN_TOKENS: cached tokens from which it is taken (break-even measured near 32K)
     int64_t stream_min_tokens = 65536;   // SK_STREAM_MIN_TOKENS: cached tokens from which the 128-row instances load non-temporal
     bool fuse = false;                   // SK_FUSE=1: single-session calls merge their split partials inside the attention kernel
     bool fuse_list = false;              // batched calls too (the last workgroup of a unit merges alone)

@@ -43,7 +43,7 @@ def test_bf16_gqa_ragged_appends_and_queries(block_tokens, env):
     appends of ragged lengths (several row tiles, partial tiles, single tokens, block-straddling),
     then queries of several lengths in both modes with several split counts; once more with the
     eight-wave 128-row instance and the non-temporal loads that single-session calls of 65-128 rows
-    otherwise only take from 32,768 / 65,536 cached tokens on."""
+    otherwise only take from 30,720 / 65,536 cached tokens on."""
     shape = synth.CFG2
     gen = synth.generator(2, stream=1)
     pr = Pair(shape, block_tokens=block_tokens, n_blocks=4096 // block_tokens + 8, kv_fill=0xFF, max_batch_tokens=1024, env=env)
