@@ -114,6 +114,43 @@ def test_single_session_full_context(n, L, nq, n_rows, B):
         _check_rows("32-token query B at %d" % n, out, lse, rows2, ro, rl, shape.dtype)
 
 
+def test_head_dim_64_at_70000_cached_tokens():
+    """A Llama-3.2-1B-shaped layer (32/8 heads, head_dim 64, bf16) at a length where the library takes
+    the launch configurations of the long caches (one workgroup per CU, the eight-wave 128-row instance,
+    non-temporal loads): a 256-token append, then 16-, 32- and 100-token queries on sampled rows."""
+    shape = synth.Shape("bf16", 32, 8, 64)
+    n, L = 70000, 256
+    gen = synth.generator(6, stream=21)
+    rng = np.random.default_rng(64)
+    pool = sk.Pool(shape.dtype, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, 16, n // 16 + 8, max_sessions=1,
+                   max_batch_tokens=2048)
+    ref = oracle.OracleSession(shape.dtype, shape.n_q_heads, shape.n_kv_heads, shape.head_dim)
+    sid = pool.sk_session_create()
+    _build(pool, sid, ref, n - L, shape, gen)
+    q, k, v = synth.draw_qkv(gen, L, shape)
+    out, lse = pool.sk_session_append(sid, dev(q), dev(k), dev(v))
+    assert pool.sk_pool_last_launch()["kernel_variant"] != 0
+    rows = _sample_rows(rng, L, shape, extra=16, tile_rows=128)      # head_dim 64 has no 256-row tile
+    ro, rl = ref.append(synth.to_raw(q), synth.to_raw(k), synth.to_raw(v), rows=rows)
+    _check_rows("append at %d" % (n - L), out, lse, rows, ro, rl, shape.dtype)
+    for first in (0, n - 1024):
+        kc, vc = pool.sk_session_gather(sid, first, 1024)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(synth.to_raw(kc.cpu()), ref.K[first:first + 1024])
+        np.testing.assert_array_equal(synth.to_raw(vc.cpu()), ref.V[first:first + 1024])
+    for nq in (16, 32, 100):
+        qq, kq, vq = synth.draw_qkv(gen, nq, shape)
+        rows = _sample_rows(rng, nq, shape, extra=4, tile_rows=min(128, _tile_rows(nq, shape)))
+        rows = [rows[i] for i in sorted(rng.choice(len(rows), size=min(16, len(rows)), replace=False))]
+        out, lse = pool.sk_session_query(sid, dev(qq))
+        assert pool.sk_pool_last_launch()["workgroups"] >= 256
+        ro, rl = ref.query(synth.to_raw(qq), rows=rows)
+        _check_rows("query A, %d tokens" % nq, out, lse, rows, ro, rl, shape.dtype)
+        out, lse = pool.sk_session_query(sid, dev(qq), dev(kq), dev(vq))
+        ro, rl = ref.query(synth.to_raw(qq), synth.to_raw(kq), synth.to_raw(vq), rows=rows)
+        _check_rows("query B, %d tokens" % nq, out, lse, rows, ro, rl, shape.dtype)
+
+
 def test_registered_question_batch_at_65536():
     """Workload 5: 64 questions of 16 + 8 tokens against a 65,536-token session at the 70B-layer shape,
     after a 256-token append; sampled rows of the prefix and of several questions."""
