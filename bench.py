@@ -248,6 +248,8 @@ def main():
             extras["cfg4_multi_tenant_step"] = multi_tenant(sk)
         if want("cfg1_fp32_small"):
             extras["cfg1_fp32_small"] = fp32_small(sk)
+        if want("head_dim_64_32k"):
+            extras["head_dim_64_32k"] = head_dim_64(sk)
         if want("sliding_window_32k"):
             extras["sliding_window_32k"] = sliding_window(sk)
         if want("fork_cost"):
@@ -457,6 +459,39 @@ def latency_vs_cached_tokens(sk, ceilings, nq=32):
     return {"query_tokens": nq, "points": points, "timing": "stream",
             "fit_cold": {"fixed_us": float(icpt), "us_per_MB": float(slope * 1e6), "implied_GBps": float(1.0 / slope / 1e3)},
             "note": "the 2,600-token rotation holds 1.36 GB in 128 sessions; shorter caches leave most CUs idle (at least 256 keys per workgroup)"}
+
+
+def head_dim_64(sk, n=32768, L=256, reps=100):
+    """A Llama-3.2-1B-shaped layer (bf16, 32/8 heads, head_dim 64) at 32,768 cached tokens: 256-token
+    append and 16- / 32-token queries, rotating over sessions that hold more than 1 GiB together.
+    Half the bytes and half the matrix work of the headline shape per token; the softmax work is the same."""
+    shape = synth.Shape("bf16", 32, 8, 64)
+    n_sessions = rotation_sessions(n * shape.kv_bytes_per_token)
+    pool = sk.Pool(shape.dtype, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, 16, n_sessions * (n // 16 + 2),
+                   max_sessions=n_sessions, max_batch_tokens=1024)
+    sids = build_sessions(pool, shape, n - L, n_sessions, synth.generator(2, stream=70))
+    qa, ka, va = [t.cuda() for t in synth.draw_qkv(synth.generator(2, stream=71), L, shape)]
+    out_a = torch.empty((L, shape.n_q_heads, shape.head_dim), dtype=torch.float32, device="cuda")
+    lse_a = torch.empty((L, shape.n_q_heads), dtype=torch.float32, device="cuda")
+
+    def app(i):
+        sid = sids[i % n_sessions]
+        pool.sk_session_append(sid, qa, ka, va, out=out_a, lse=lse_a)
+        pool.sk_session_truncate(sid, n - L)
+    ramp(app, 50.0, 8)
+    a_us = stream_time_us(app, reps, warm=n_sessions)
+    for sid in sids:
+        pool.sk_session_append(sid, None, ka, va)
+    res = {"cached_tokens": n, "append_tokens": L, "append_us": a_us,
+           "append_tflops": append_flops(shape, n - L, L) / (a_us * 1e-6) / 1e12,
+           "append_mfma_frac": append_flops(shape, n - L, L) / (a_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+           "timing": "stream (commit + attention + combine per call; queries cold)"}
+    for nq in (16, 32):
+        q_us = stream_time_us(lambda i: pool.sk_session_query(sids[i % n_sessions], qa[:nq], out=out_a[:nq], lse=lse_a[:nq]), reps, warm=n_sessions)
+        qb = query_bytes(shape, n, nq, 16)
+        res["query_%d_tokens" % nq] = {"latency_us": q_us, "kv_GBps": qb / (q_us * 1e-6) / 1e9, "hbm_frac": qb / (q_us * 1e-6) / 1e9 / HBM_PEAK_GBPS}
+    pool.close()
+    return res
 
 
 def fp32_small(sk, reps=200):

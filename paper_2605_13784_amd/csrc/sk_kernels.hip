@@ -352,12 +352,13 @@ __device__ __forceinline__ sk_tile_blocks sk_lookup_tile(const sk_seg& g, int t0
 // and the 16-key group's offset inside a block of more than 16 tokens is added to those.
 // In LDS the sixteen 1 KiB units of a tile (K units 0-7, V^T units 8-15) lie US bytes apart, with
 // the same unit of the other tiles of the ring in between; `unit_addr` is the address of unit `sub`.
-// With head_dim 64 the tile keeps this LDS layout and fills half of it: a K row holds 128 bytes, so
-// the lanes of the upper eight chunk positions sit the K load out (`k_lane`: a direct-to-LDS load
-// moves the active lanes only), and V^T has 64 dims, so only the waves with sub < 2 load it (`v_wave`).
+// With head_dim 64 a tile has half the bytes.  K: rows of 128 bytes, eight to a 1 KiB unit, units
+// 0-3; one load per wave and tile (wave sub loads rows 8 (sub & 1) .. + 7 of group sub >> 1, `k_group`,
+// into unit sub).  V^T: the same units as with head_dim 128, of which 64 dims fill two per group, so
+// only the waves with sub < 2 load it (`v_wave`).
 template <unsigned US, int J, int D>
 __device__ __forceinline__ void sk_issue_group(const sk_seg& g, int t0, int last_group, uint32_t blk,
-                                               unsigned unit_addr, unsigned koff, unsigned voff, bool k_lane, bool v_wave)
+                                               unsigned unit_addr, unsigned koff, unsigned voff, int k_group, bool v_wave)
 {
     constexpr int LOG2_TOK_BYTES = D == 128 ? 8 : 7;       // K bytes per token and head = V^T bytes per token
     int tg = t0 + 16 * J;
@@ -369,19 +370,21 @@ __device__ __forceinline__ void sk_issue_group(const sk_seg& g, int t0, int last
         voff += slot0 << LOG2_TOK_BYTES;          // V^T: 4 (2) KiB per 16-token group
     }
     if (g.once) {       // uniform over the workgroup
-        if (D == 128 || k_lane) sk_dma16<J * 4 * US, true>(bb, koff, unit_addr);
+        if (D == 128) sk_dma16<J * 4 * US, true>(bb, koff, unit_addr);
+        else if (k_group == J) sk_dma16<0, true>(bb, koff, unit_addr);
         if (D == 128 || v_wave) sk_dma16<(8 + J * 4) * US, true>(bb, voff, unit_addr);
     } else {
-        if (D == 128 || k_lane) sk_dma16<J * 4 * US, false>(bb, koff, unit_addr);
+        if (D == 128) sk_dma16<J * 4 * US, false>(bb, koff, unit_addr);
+        else if (k_group == J) sk_dma16<0, false>(bb, koff, unit_addr);
         if (D == 128 || v_wave) sk_dma16<(8 + J * 4) * US, false>(bb, voff, unit_addr);
     }
 }
 template <unsigned US, int D>
 __device__ __forceinline__ void sk_issue_tile(const sk_seg& g, int t0, int last_group, const sk_tile_blocks& tb,
-                                              unsigned unit_addr, unsigned koff, unsigned voff, bool k_lane, bool v_wave)
+                                              unsigned unit_addr, unsigned koff, unsigned voff, int k_group, bool v_wave)
 {
-    sk_issue_group<US, 0, D>(g, t0, last_group, tb.blk[0], unit_addr, koff, voff, k_lane, v_wave);
-    sk_issue_group<US, 1, D>(g, t0, last_group, tb.blk[1], unit_addr, koff, voff, k_lane, v_wave);
+    sk_issue_group<US, 0, D>(g, t0, last_group, tb.blk[0], unit_addr, koff, voff, k_group, v_wave);
+    sk_issue_group<US, 1, D>(g, t0, last_group, tb.blk[1], unit_addr, koff, voff, k_group, v_wave);
 }
 
 template <int NRG, int NPH, int NSS, int D>
@@ -488,8 +491,9 @@ __device__ __forceinline__ void sk_attn_bf16_body(const sk_launch P)
     sk_lds_cptr kptr[8];
     sk_lds_cptr vptr[4];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks)       // K row tau is row tau % 4 of unit tau / 4
-        kptr[ks] = (sk_lds_cptr)lds + SK_SLOT_OFF(0, ph * TPW) + (tau >> 2) * US + (tau & 3) * 256 + (((ks * 2 + kg) ^ (tau & (D / 8 - 1))) << 4);
+    for (int ks = 0; ks < 8; ++ks)       // K row tau is row tau % 4 of unit tau / 4 (head_dim 64: row tau % 8 of unit tau / 8)
+        kptr[ks] = D == 128 ? (sk_lds_cptr)lds + SK_SLOT_OFF(0, ph * TPW) + (tau >> 2) * US + (tau & 3) * 256 + (((ks * 2 + kg) ^ (tau & 15)) << 4)
+                            : (sk_lds_cptr)lds + SK_SLOT_OFF(0, ph * TPW) + (tau >> 3) * US + (tau & 7) * 128 + (((ks * 2 + kg) ^ (tau & 7)) << 4);
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
         const int dd = mt * 32 + r;
@@ -509,11 +513,12 @@ __device__ __forceinline__ void sk_attn_bf16_body(const sk_launch P)
         const int lim_row = p_row < seg_last_pos ? p_row : seg_last_pos;
 
         // lane-dependent parts of the DMA source addresses for this segment
-        // (head_dim 64: a K row has eight 16-byte chunks, swizzled among themselves, and the lanes of the
-        // upper eight chunk positions load nothing; V^T has dims for the first two waves only)
-        const int krow = sub * 4 + (lane >> 4);
-        const unsigned koff = (unsigned)(krow * (D * 2) + (((lane & 15) ^ (krow & (D / 8 - 1))) << 4));
-        const bool k_lane = (lane & 15) < D / 8;
+        // (head_dim 64: lane -> (row rr of eight, chunk position of eight), source chunk (position ^ rr),
+        // the wave's rows being 8 (sub & 1) .. + 7 of group sub >> 1; V^T has dims for the first two waves only)
+        const int krow = D == 128 ? sub * 4 + (lane >> 4) : (sub & 1) * 8 + (lane >> 3);
+        const unsigned koff = D == 128 ? (unsigned)(krow * 256 + (((lane & 15) ^ krow) << 4))
+                                       : (unsigned)(krow * 128 + (((lane & 7) ^ (krow & 7)) << 4));
+        const int k_group = sub >> 1;
         const int vdd = sub * 32 + (lane >> 1);
         const unsigned voff = (unsigned)(g.v_off + vdd * 32 + ((((lane & 1) ^ ((vdd >> 3) & 1))) << 4));
         const bool v_wave = sub < NMT;
@@ -659,7 +664,7 @@ __device__ __forceinline__ void sk_attn_bf16_body(const sk_launch P)
                         if (NLG > 1 && (p % NLG) != lg) continue;
                         const int t0 = g.begin + a * g.step + p * SK_TILE;
                         const sk_tile_blocks tb = sk_lookup_tile(g, t0, last_group);
-                        sk_issue_tile<US, D>(g, t0, last_group, tb, unit_base + SK_SLOT_OFF(a, p), koff, voff, k_lane, v_wave);
+                        sk_issue_tile<US, D>(g, t0, last_group, tb, unit_base + SK_SLOT_OFF(a, p), koff, voff, k_group, v_wave);
                     }
                 }
             }
@@ -688,7 +693,7 @@ __device__ __forceinline__ void sk_attn_bf16_body(const sk_launch P)
                     for (int p = 0; p < TPI; ++p) {
                         if (NLG > 1 && (p % NLG) != lg) continue;
                         sk_issue_tile<US, D>(g, g.begin + (it + NSS - 1) * g.step + p * SK_TILE, last_group, nb[p],
-                                                       unit_base + SK_SLOT_OFF((slot + NSS - 1) % NSS, p), koff, voff, k_lane, v_wave);
+                                                       unit_base + SK_SLOT_OFF((slot + NSS - 1) % NSS, p), koff, voff, k_group, v_wave);
                     }
                     if (it + NSS < niter) {
 #pragma unroll
@@ -740,7 +745,7 @@ __device__ __forceinline__ void sk_attn_bf16_body(const sk_launch P)
                 if (a < ahead && a < niter) {
                     const int t0 = g.begin + a * g.step + my_tile * SK_TILE;
                     const sk_tile_blocks tb = sk_lookup_tile(g, t0, last_group);
-                    sk_issue_tile<US, D>(g, t0, last_group, tb, unit_base + SK_SLOT_OFF(a, my_tile), koff, voff, k_lane, v_wave);
+                    sk_issue_tile<US, D>(g, t0, last_group, tb, unit_base + SK_SLOT_OFF(a, my_tile), koff, voff, k_group, v_wave);
                 }
             }
             sk_tile_blocks nb = sk_lookup_tile(g, g.begin + ahead * g.step + my_tile * SK_TILE, last_group);
@@ -757,7 +762,7 @@ __device__ __forceinline__ void sk_attn_bf16_body(const sk_launch P)
                 const int i = j + ahead;
                 if (i < niter) {
                     sk_issue_tile<US, D>(g, g.begin + i * g.step + my_tile * SK_TILE, last_group, nb,
-                                                   unit_base + SK_SLOT_OFF(i & 3, my_tile), koff, voff, k_lane, v_wave);
+                                                   unit_base + SK_SLOT_OFF(i & 3, my_tile), koff, voff, k_group, v_wave);
                     if (i + 1 < niter) nb = sk_lookup_tile(g, g.begin + (i + 1) * g.step + my_tile * SK_TILE, last_group);
                 }
             };
